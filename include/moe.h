@@ -1,0 +1,165 @@
+/*
+ * libmoe -- one GPU's share of a Mixture-of-Experts layer on MI355X (gfx950).
+ *
+ * The share follows the paper's statement of the MoE block under hybrid
+ * TP-EP parallelism: tokens are routed to their top-k activated experts
+ * (Sec. III-B-2 "A2A"; the `route` step of Alg. 2), sent to the device that
+ * hosts the expert ("Dispatch", Sec. II), pushed through that expert's MLP,
+ * whose weights are an intra-node TP slice (Sec. II "TP", Sec. III-C), and
+ * returned along the original route weighted by the top-k weights
+ * ("Combine", Sec. II; Alg. 1 `Y_i <- Y_i + topk_weights(S_i)`), giving the
+ * partial sum that the intra-node all-reduce completes (Sec. III-B-2 "AR").
+ * The exchanges themselves (A2A, AR) are outside this library: it builds the
+ * buffer the A2A would carry and the tensor the AR would reduce.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers unless marked "host".  The caller
+ *    owns every buffer, including the workspace; the library never allocates,
+ *    frees or synchronises.  All work is enqueued on `stream` (a hipStream_t
+ *    passed as void*; NULL is the default stream).
+ *  - Tensors are dense and row-major.  Device pointers must be 16-byte aligned.
+ *  - Outputs are overwritten.  Rows / entries beyond the valid count of a
+ *    capacity-sized output are unspecified.
+ *  - Arguments are validated on the host before anything is launched; on any
+ *    error nothing is enqueued and outputs are untouched.  T == 0 returns
+ *    MOE_OK and launches nothing.
+ *  - The return value is the only error channel; nothing is thrown.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = 1, /* NULL / misaligned pointer, negative size, inconsistent config */
+  MOE_ERR_UNSUPPORTED = 2, /* dtype combination or shape the kernels do not cover          */
+  MOE_ERR_WORKSPACE = 3,   /* ws_bytes smaller than moe_workspace_bytes()                   */
+  MOE_ERR_DEVICE = 4       /* a launch failed (hipGetLastError after the launch)            */
+} moe_status;
+
+typedef enum {
+  MOE_F32 = 0,
+  MOE_BF16 = 1,
+  MOE_FP8_E4M3_B128 = 2 /* OCP e4m3 codes + one fp32 scale per 128x128 block (weights only) */
+} moe_dtype;
+
+typedef enum { MOE_SCORE_SOFTMAX = 0, MOE_SCORE_SIGMOID = 1 } moe_score_fn;
+
+/*
+ * Layer description.  Symbols follow the paper where it has them: h = hidden,
+ * k = experts activated per token, d_EP / d_TP enter through the expert range
+ * and the intermediate slice.
+ */
+typedef struct {
+  int32_t hidden;        /* H, multiple of 8                                              */
+  int32_t n_experts;     /* E, global routed experts                                      */
+  int32_t top_k;         /* k, 1 <= k <= 32, k <= E                                       */
+  int32_t score_fn;      /* moe_score_fn                                                  */
+  int32_t renormalize;   /* 1: weights of the k picked experts sum to routed_scale        */
+  float routed_scale;    /* multiplies the weights (1.0, or 2.5 for the DeepSeek shape)   */
+  int32_t n_groups;      /* G; 1 = no group limit; E % G == 0                             */
+  int32_t topk_groups;   /* groups kept, 1 <= topk_groups <= G                            */
+  int32_t group_score_n; /* group score = sum of this many largest keys of the group     */
+  int32_t expert_lo;     /* this GPU hosts global experts [expert_lo, expert_hi)          */
+  int32_t expert_hi;
+  int32_t inter_local;   /* I_loc = I / d_TP, multiple of 8 (128 for fp8 weights)         */
+  int32_t act_dtype;     /* MOE_F32 or MOE_BF16: x, xs, ys, gate weights                  */
+  int32_t weight_dtype;  /* MOE_F32 (with F32 act), MOE_BF16 or MOE_FP8_E4M3_B128         */
+} moe_config;
+
+/* Upper bound, in bytes, of the workspace any entry point needs for T tokens
+ * (0 if the config is invalid).  Host-only, launches nothing. */
+size_t moe_workspace_bytes(const moe_config* cfg, int32_t T);
+
+/* Static description of a status code (host pointer, never NULL). */
+const char* moe_status_string(moe_status s);
+
+/*
+ * Gate scoring and top-k routing (Sec. III-B-2: every token goes to its top-k
+ * activated experts; Alg. 2: the expert map is computed from local states).
+ *   logit z[t,e]  = sum_h x[t,h] * gate_w[e,h]  (+ logit_bias[e])
+ *   score         = softmax_e(z)  or  sigmoid(z)
+ *   selection key = z (softmax)   or  sigmoid(z) + select_bias[e]
+ *   group limit   = keep the topk_groups groups with the largest sum of their
+ *                   group_score_n largest keys; other experts are ineligible
+ *   topk_ids[t,:] = the k eligible experts with the largest keys, in descending
+ *                   key order; ties go to the lowest expert (group) index
+ *   topk_w[t,j]   = score (without select_bias), divided by the sum over the
+ *                   k picked when renormalize, times routed_scale
+ * The ids are those of exact arithmetic on the stored inputs: keys are first
+ * computed fast (bf16 MFMA, fp32 accumulation in short chains) and every token
+ * whose decisive key gaps are within the error bound of that computation is
+ * re-scored in fp64.  After the call the first int32 of `ws` holds the number
+ * of tokens that were re-scored.
+ *   x          [T,H]  act dtype            gate_w [E,H] act dtype
+ *   logit_bias [E] fp32 or NULL            select_bias [E] fp32 or NULL
+ *   logits_in  [T,E] fp32 or NULL: when given the dot products are skipped and
+ *              these are the logits (x and gate_w may then be NULL)
+ *   topk_ids   out [T,k] int32 global expert ids     topk_w out [T,k] fp32
+ */
+moe_status moe_route(const moe_config* cfg, int32_t T, const void* x, const void* gate_w,
+                     const float* logit_bias, const float* select_bias,
+                     const float* logits_in, int32_t* topk_ids, float* topk_w, void* ws,
+                     size_t ws_bytes, void* stream);
+
+/*
+ * Dispatch (Sec. II "EP": each token is sent to the device hosting its
+ * expert; Alg. 2: per-destination lists built from the expert map).  Builds
+ * the expert-contiguous send buffer for the assignments whose expert is in
+ * [expert_lo, expert_hi).  Flat assignment index a = t*k + j.
+ *   counts  out [E_loc]     assignments per local expert
+ *   offsets out [E_loc+1]   exclusive scan of counts; offsets[E_loc] = A_loc
+ *   perm    out [T*k]       first A_loc valid: position -> a; experts ascending,
+ *                           inside an expert ascending a (stable, atomic-free)
+ *   inv     out [T*k]       a -> position, or -1 when the expert is not local
+ *   xs      out [T*k, H]    act dtype; first A_loc rows valid: xs[pos] = x[perm[pos]/k]
+ * counts/offsets stay on the device; later calls read them there.
+ */
+moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
+                        const int32_t* topk_ids, int32_t* counts, int32_t* offsets,
+                        int32_t* perm, int32_t* inv, void* xs, void* ws, size_t ws_bytes,
+                        void* stream);
+
+/*
+ * Grouped expert MLP (Sec. II: each expert is an independent MLP; under TP the
+ * projections are sliced and the partial results are summed afterwards).  For
+ * expert e in [0, n_experts_here) and every row r in [offsets[e], offsets[e+1]):
+ *   ys[r,:] = w_down[e] * ( silu(w_gate[e] * xs[r,:]) .* (w_up[e] * xs[r,:]) )
+ * with fp32 accumulation; the intermediate is held in the act dtype.
+ *   xs      [rows_capacity, H] act dtype        offsets [n_experts_here+1] int32 (device)
+ *   w_gate, w_up [n, I_loc, H]   w_down [n, H, I_loc]   weight dtype
+ *   s_gate, s_up [n, I_loc/128, ceil(H/128)]  s_down [n, ceil(H/128), I_loc/128]
+ *           fp32 block scales, required for MOE_FP8_E4M3_B128, else NULL
+ *   ys      out [rows_capacity, H] act dtype
+ * rows_capacity bounds offsets[n]; rows beyond offsets[n] are not touched.
+ * The shared expert is the same call with n_experts_here = 1, offsets = {0,T},
+ * xs = x.
+ */
+moe_status moe_expert_ffn(const moe_config* cfg, int32_t n_experts_here, const void* xs,
+                          const int32_t* offsets, int32_t rows_capacity, const void* w_gate,
+                          const void* w_up, const void* w_down, const float* s_gate,
+                          const float* s_up, const float* s_down, void* ys, void* ws,
+                          size_t ws_bytes, void* stream);
+
+/*
+ * Combine (Sec. II: results return along the original route; Alg. 1: they are
+ * weighted by the top-k weights) into the partial sum the intra-node
+ * all-reduce would finish (Sec. III-B-2 "AR"):
+ *   out[t,:] = sum_{j : inv[t*k+j] >= 0} topk_w[t,j] * ys[inv[t*k+j],:]  (+ shared_ys[t,:])
+ * summed over ascending j in fp32.
+ *   ys [>= A_loc, H] act dtype   inv [T*k]   topk_w [T,k]
+ *   shared_ys [T,H] act dtype or NULL       out [T,H] fp32, overwritten
+ */
+moe_status moe_combine(const moe_config* cfg, int32_t T, const void* ys, const int32_t* inv,
+                       const float* topk_w, const void* shared_ys, float* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

@@ -107,12 +107,21 @@ def route(x, gate_w, k, score_fn="softmax", renormalize=True, routed_scale=1.0,
     return (ids, w, margin, logits) if return_logits else (ids, w, margin)
 
 
-def dispatch(ids, x, e_lo, e_hi):
+def dispatch(ids, x, e_lo, e_hi, want_xs=True):
     """Expert-contiguous buffer build.  Returns counts, offsets, perm (length
-    A_loc), inv [T*k], xs float32 [A_loc,H]."""
+    A_loc), inv [T*k], xs float32 [A_loc,H] (None when want_xs is False)."""
     ids = np.ascontiguousarray(ids, np.int32)
-    xf = decode(x)
     T, k = ids.shape
+    if not want_xs:
+        E_loc = e_hi - e_lo
+        counts = np.empty((E_loc,), np.int32)
+        offsets = np.empty((E_loc + 1,), np.int32)
+        perm = np.full((T * k,), -1, np.int32)
+        inv = np.empty((T * k,), np.int32)
+        _load().oracle_dispatch(T, k, 0, e_lo, e_hi, _p(ids), None, _p(counts), _p(offsets),
+                                _p(perm), _p(inv), None)
+        return counts, offsets, perm[:int(offsets[-1])].copy(), inv, None
+    xf = decode(x)
     H = xf.shape[1]
     E_loc = e_hi - e_lo
     counts = np.empty((E_loc,), np.int32)

@@ -1,0 +1,117 @@
+// Combine: return the expert outputs along the original route, weighted by the
+// top-k weights, into the fp32 partial sum awaiting the intra-node all-reduce
+// (Sec. II "Combine"; Alg. 1 `Y_i <- Y_i + topk_weights(S_i)`).
+//
+// Gather-by-token: one wavefront owns a token, walks the row in 16-byte pieces
+// and adds the token's local expert rows in ascending j, so there are no
+// atomics and the result does not depend on scheduling.  Bandwidth-bound:
+// reads A_loc*H (+T*H shared) activations, writes T*H fp32.
+#include "moe_internal.h"
+
+namespace moe {
+
+namespace {
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+__device__ __forceinline__ void fma8(float (&acc)[8], float w, const uint4& v) {
+  acc[0] = fmaf(w, bf16_lo(v.x), acc[0]);
+  acc[1] = fmaf(w, bf16_hi(v.x), acc[1]);
+  acc[2] = fmaf(w, bf16_lo(v.y), acc[2]);
+  acc[3] = fmaf(w, bf16_hi(v.y), acc[3]);
+  acc[4] = fmaf(w, bf16_lo(v.z), acc[4]);
+  acc[5] = fmaf(w, bf16_hi(v.z), acc[5]);
+  acc[6] = fmaf(w, bf16_lo(v.w), acc[6]);
+  acc[7] = fmaf(w, bf16_hi(v.w), acc[7]);
+}
+
+// bf16 rows: a piece is 8 elements (16 B in, 32 B out).
+__global__ __launch_bounds__(256) void combine_bf16_kernel(
+    const uint4* __restrict__ ys, const int32_t* __restrict__ inv, const float* __restrict__ w,
+    const uint4* __restrict__ shared_ys, float4* __restrict__ out, int T, int k, int row8) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (t >= T) return;
+  int pos = -1;
+  float wt = 0.f;
+  if (lane < k) {
+    pos = inv[size_t(t) * k + lane];
+    wt = w[size_t(t) * k + lane];
+  }
+  const uint64_t have = __ballot(pos >= 0);
+  for (int c = lane; c < row8; c += 64) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    uint64_t m = have;
+    while (m) {                               // ascending j
+      const int j = __ffsll((unsigned long long)m) - 1;
+      m &= m - 1;
+      const int p = __shfl(pos, j);
+      const float wj = __shfl(wt, j);
+      const uint4 v = ys[size_t(p) * row8 + c];
+      fma8(acc, wj, v);
+    }
+    if (shared_ys) {
+      const uint4 v = shared_ys[size_t(t) * row8 + c];
+      fma8(acc, 1.0f, v);
+    }
+    float4* o = out + (size_t(t) * row8 + c) * 2;
+    o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+  }
+}
+
+// fp32 rows: a piece is 4 elements.
+__global__ __launch_bounds__(256) void combine_f32_kernel(
+    const float4* __restrict__ ys, const int32_t* __restrict__ inv, const float* __restrict__ w,
+    const float4* __restrict__ shared_ys, float4* __restrict__ out, int T, int k, int row4) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (t >= T) return;
+  int pos = -1;
+  float wt = 0.f;
+  if (lane < k) {
+    pos = inv[size_t(t) * k + lane];
+    wt = w[size_t(t) * k + lane];
+  }
+  const uint64_t have = __ballot(pos >= 0);
+  for (int c = lane; c < row4; c += 64) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    uint64_t m = have;
+    while (m) {
+      const int j = __ffsll((unsigned long long)m) - 1;
+      m &= m - 1;
+      const int p = __shfl(pos, j);
+      const float wj = __shfl(wt, j);
+      const float4 v = ys[size_t(p) * row4 + c];
+      acc.x = fmaf(wj, v.x, acc.x);
+      acc.y = fmaf(wj, v.y, acc.y);
+      acc.z = fmaf(wj, v.z, acc.z);
+      acc.w = fmaf(wj, v.w, acc.w);
+    }
+    if (shared_ys) {
+      const float4 v = shared_ys[size_t(t) * row4 + c];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    out[size_t(t) * row4 + c] = acc;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_combine(const moe_config& c, int T, const void* ys, const int32_t* inv,
+                          const float* w, const void* shared_ys, float* out, hipStream_t s) {
+  const dim3 grid((T + 3) / 4), block(256);
+  if (c.act_dtype == MOE_BF16) {
+    hipLaunchKernelGGL(combine_bf16_kernel, grid, block, 0, s, static_cast<const uint4*>(ys), inv,
+                       w, static_cast<const uint4*>(shared_ys), reinterpret_cast<float4*>(out), T,
+                       c.top_k, c.hidden / 8);
+  } else {
+    hipLaunchKernelGGL(combine_f32_kernel, grid, block, 0, s, static_cast<const float4*>(ys), inv,
+                       w, static_cast<const float4*>(shared_ys), reinterpret_cast<float4*>(out), T,
+                       c.top_k, c.hidden / 4);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,395 @@
+// Grouped expert MLP (Sec. II: every expert is an independent MLP; under TP
+// its projections are sliced and the partial results summed afterwards).
+//
+//   GEMM-1  hmid[r,:] = silu(xs[r,:] Wgate_e^T) .* (xs[r,:] Wup_e^T)   r in expert e's rows
+//   GEMM-2  ys[r,:]   = hmid[r,:] Wdown_e^T
+//
+// Both are "TN" GEMMs (activations [rows,K] and weights [N,K], K contiguous)
+// over ragged row groups whose bounds live on the device.  A one-block
+// prologue turns `offsets` into a table of M tiles (expert, first row, end
+// row); the GEMM grid is sized for the worst case and workgroups past the
+// table's length exit at once, so there is no host round trip.
+//
+// bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation, LDS double buffer,
+// K step 64; LDS tiles are [row][8 pieces of 16 B], piece index XOR (row&7).
+// GEMM-1 loads a gate tile and the matching up tile so that one lane holds g
+// and u of the same element and the SwiGLU is applied in registers.
+// fp8 weights: e4m3 codes are widened to bf16 (exact) on the way into LDS; the
+// 128x128 block scale multiplies the fp32 partial sum of each 128-deep K block.
+#include "moe_internal.h"
+
+namespace moe {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BK = 64;
+
+__device__ __forceinline__ int swz(int row, int piece) { return row * 8 + (piece ^ (row & 7)); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  return __builtin_bit_cast(uint16_t, (__bf16)f);   // round to nearest even
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) {
+  return g / (1.0f + __expf(-g)) * u;
+}
+
+// ------------------------------------------------------------- tile table
+// tiles[0] = number of M tiles; then (expert, first row, end row) per tile.
+__global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restrict__ offsets,
+                                                       int n_experts, int bm, int rows_capacity,
+                                                       int32_t* __restrict__ tiles, int max_tiles) {
+  __shared__ int32_t start[513];
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int e = 0; e < n_experts; ++e) {
+      int lo = offsets[e], hi = offsets[e + 1];
+      lo = lo < 0 ? 0 : lo;
+      hi = hi > rows_capacity ? rows_capacity : hi;
+      start[e] = run;
+      run += hi > lo ? (hi - lo + bm - 1) / bm : 0;
+    }
+    start[n_experts] = run;
+    tiles[0] = run < max_tiles ? run : max_tiles;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < n_experts; e += blockDim.x) {
+    int lo = offsets[e], hi = offsets[e + 1];
+    lo = lo < 0 ? 0 : lo;
+    hi = hi > rows_capacity ? rows_capacity : hi;
+    int t = start[e];
+    for (int r = lo; r < hi && t < max_tiles; r += bm, ++t) {
+      tiles[1 + 3 * t] = e;
+      tiles[2 + 3 * t] = r;
+      tiles[3 + 3 * t] = (r + bm < hi) ? r + bm : hi;
+    }
+  }
+}
+
+// ------------------------------------------------------------ MFMA GEMM
+// C[rows, N] = A[rows, K] * B_e[N, K]^T over the M tiles of the table.
+// DUAL: B0 = gate, B1 = up, C = silu(A B0^T) .* (A B1^T).
+template <int BM, int BN, int WM, int WN, bool DUAL, bool FP8>
+__global__ __launch_bounds__(256) void ffn_gemm_kernel(
+    const uint16_t* __restrict__ A, const void* __restrict__ B0, const void* __restrict__ B1,
+    const float* __restrict__ S0, const float* __restrict__ S1, uint16_t* __restrict__ C, int N,
+    int K, const int32_t* __restrict__ tiles) {
+  constexpr int BROWS = DUAL ? 2 * BN : BN;
+  constexpr int WGN = BN / WN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int NACC = DUAL ? 2 : 1;
+  static_assert((BM / WM) * WGN == 4, "four wavefronts");
+  constexpr int A_PER = BM * 8 / 256;
+  constexpr int B_PER = FP8 ? BROWS * 4 / 256 : BROWS * 8 / 256;
+
+  // dynamic LDS: A double buffer, then B double buffer
+  extern __shared__ uint4 smem[];
+  uint4 (*As)[BM * 8] = reinterpret_cast<uint4 (*)[BM * 8]>(smem);
+  uint4 (*Bs)[BROWS * 8] = reinterpret_cast<uint4 (*)[BROWS * 8]>(smem + 2 * BM * 8);
+
+  const int n_ntiles = (N + BN - 1) / BN;
+  const int mtile = blockIdx.x / n_ntiles, ntile = blockIdx.x % n_ntiles;
+  if (mtile >= tiles[0]) return;
+  const int e = tiles[1 + 3 * mtile], row0 = tiles[2 + 3 * mtile], row1 = tiles[3 + 3 * mtile];
+  const int n0 = ntile * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int ksteps = (K + BK - 1) / BK;
+  const size_t wbytes = FP8 ? 1 : 2;
+  const char* Be0 = static_cast<const char*>(B0) + size_t(e) * N * K * wbytes;
+  const char* Be1 = DUAL ? static_cast<const char*>(B1) + size_t(e) * N * K * wbytes : nullptr;
+
+  uint4 ra[A_PER], rb[B_PER];
+  auto gload = [&](int ks) {
+    {
+      const int lrow = tid >> 3, piece = tid & 7;
+      const int kcol = ks * BK + piece * 8;
+#pragma unroll
+      for (int i = 0; i < A_PER; ++i) {
+        int r = row0 + lrow + 32 * i;
+        r = r < row1 ? r : row1 - 1;
+        ra[i] = kcol < K ? *reinterpret_cast<const uint4*>(A + size_t(r) * K + kcol)
+                         : make_uint4(0, 0, 0, 0);
+      }
+    }
+    if (FP8) {
+      const int lrow = tid >> 2, piece = tid & 3;    // 16 codes per piece
+      const int kcol = ks * BK + piece * 16;
+#pragma unroll
+      for (int i = 0; i < B_PER; ++i) {
+        const int lr = lrow + 64 * i;
+        const char* base = (DUAL && lr >= BN) ? Be1 : Be0;
+        int n = n0 + ((DUAL && lr >= BN) ? lr - BN : lr);
+        n = n < N ? n : N - 1;
+        rb[i] = kcol < K ? *reinterpret_cast<const uint4*>(base + size_t(n) * K + kcol)
+                         : make_uint4(0, 0, 0, 0);
+      }
+    } else {
+      const int lrow = tid >> 3, piece = tid & 7;
+      const int kcol = ks * BK + piece * 8;
+#pragma unroll
+      for (int i = 0; i < B_PER; ++i) {
+        const int lr = lrow + 32 * i;
+        const char* base = (DUAL && lr >= BN) ? Be1 : Be0;
+        int n = n0 + ((DUAL && lr >= BN) ? lr - BN : lr);
+        n = n < N ? n : N - 1;
+        rb[i] = kcol < K ? *reinterpret_cast<const uint4*>(base + (size_t(n) * K + kcol) * 2)
+                         : make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto lstore = [&](int buf) {
+    {
+      const int lrow = tid >> 3, piece = tid & 7;
+#pragma unroll
+      for (int i = 0; i < A_PER; ++i) As[buf][swz(lrow + 32 * i, piece)] = ra[i];
+    }
+    if (FP8) {
+      const int lrow = tid >> 2, piece = tid & 3;
+#pragma unroll
+      for (int i = 0; i < B_PER; ++i) {
+        const uint32_t src[4] = {rb[i].x, rb[i].y, rb[i].z, rb[i].w};
+        uint32_t o[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          // four e4m3 codes -> four fp32 -> upper halves (exact: 3 mantissa bits)
+          const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(src[q], false);
+          const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(src[q], true);
+          o[2 * q] = (__float_as_uint(lo[0]) >> 16) | (__float_as_uint(lo[1]) & 0xffff0000u);
+          o[2 * q + 1] = (__float_as_uint(hi[0]) >> 16) | (__float_as_uint(hi[1]) & 0xffff0000u);
+        }
+        const int r = lrow + 64 * i;
+        Bs[buf][swz(r, 2 * piece)] = make_uint4(o[0], o[1], o[2], o[3]);
+        Bs[buf][swz(r, 2 * piece + 1)] = make_uint4(o[4], o[5], o[6], o[7]);
+      }
+    } else {
+      const int lrow = tid >> 3, piece = tid & 7;
+#pragma unroll
+      for (int i = 0; i < B_PER; ++i) Bs[buf][swz(lrow + 32 * i, piece)] = rb[i];
+    }
+  };
+
+  f32x16 acc[NACC][TM][TN];
+  f32x16 part[FP8 ? NACC : 1][FP8 ? TM : 1][FP8 ? TN : 1];   // fp8: sum of the current K block
+#pragma unroll
+  for (int a = 0; a < NACC; ++a)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+          acc[a][i][j][q] = 0.f;
+          if constexpr (FP8) part[a][i][j][q] = 0.f;
+        }
+
+  gload(0);
+  lstore(0);
+  __syncthreads();
+  for (int ks = 0; ks < ksteps; ++ks) {
+    const int buf = ks & 1;
+    if (ks + 1 < ksteps) gload(ks + 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int piece = kk * 2 + (lane >> 5);
+      bf16x8 af[TM];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = __builtin_bit_cast(bf16x8, As[buf][swz(wm * WM + i * 32 + (lane & 31), piece)]);
+#pragma unroll
+      for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const bf16x8 bf = __builtin_bit_cast(
+              bf16x8, Bs[buf][swz(a * BN + wn * WN + j * 32 + (lane & 31), piece)]);
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            if constexpr (FP8)
+              part[a][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, part[a][i][j], 0, 0, 0);
+            else
+              acc[a][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[a][i][j], 0, 0, 0);
+          }
+        }
+    }
+    if constexpr (FP8) if ((ks & 1) == 1 || ks + 1 == ksteps) {
+      // end of a 128-deep K block: fold the block's partial sum in, scaled
+      const int kb = ks >> 1, nkb = (K + 127) / 128, nnb = (N + 127) / 128;
+#pragma unroll
+      for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          int n = n0 + wn * WN + j * 32;
+          n = n < N ? n : N - 1;
+          const float* S = a == 0 ? S0 : S1;
+          const float sc = S[(size_t(e) * nnb + n / 128) * nkb + kb];
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+              acc[a][i][j][q] = fmaf(sc, part[a][i][j][q], acc[a][i][j][q]);
+              part[a][i][j][q] = 0.f;
+            }
+        }
+    }
+    if (ks + 1 < ksteps) lstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // D layout: lane l, register q -> row (q/4)*8 + (l/32)*4 + q%4, col l%32
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * WN + j * 32 + (lane & 31);
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int row = row0 + wm * WM + i * 32 + (q >> 2) * 8 + (lane >> 5) * 4 + (q & 3);
+        float v;
+        if (DUAL) v = silu_mul(acc[0][i][j][q], acc[NACC - 1][i][j][q]);
+        else v = acc[0][i][j][q];
+        if (row < row1 && col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(v);
+      }
+    }
+}
+
+// ------------------------------------------------------------ fp32 GEMM
+// Plain VALU kernel for the fp32 configuration: 64x64 tile, 16x16 threads,
+// 4x4 outputs per thread, K step 16.
+template <bool DUAL>
+__global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ A,
+                                                     const float* __restrict__ B0,
+                                                     const float* __restrict__ B1,
+                                                     float* __restrict__ C, int N, int K,
+                                                     const int32_t* __restrict__ tiles) {
+  constexpr int TB = 64, TK = 16;
+  __shared__ float As[TK][TB + 4];
+  __shared__ float Bg[TK][TB + 4];
+  __shared__ float Bu[DUAL ? TK : 1][TB + 4];
+  const int n_ntiles = (N + TB - 1) / TB;
+  const int mtile = blockIdx.x / n_ntiles, ntile = blockIdx.x % n_ntiles;
+  if (mtile >= tiles[0]) return;
+  const int e = tiles[1 + 3 * mtile], row0 = tiles[2 + 3 * mtile], row1 = tiles[3 + 3 * mtile];
+  const int n0 = ntile * TB;
+  const float* Be0 = B0 + size_t(e) * N * K;
+  const float* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float g[4][4] = {}, u[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += TK) {
+    for (int idx = threadIdx.x; idx < TB * TK; idx += 256) {
+      const int r = idx / TK, kk = idx % TK;
+      const int k = k0 + kk;
+      int ar = row0 + r; ar = ar < row1 ? ar : row1 - 1;
+      int bn = n0 + r;   bn = bn < N ? bn : N - 1;
+      As[kk][r] = k < K ? A[size_t(ar) * K + k] : 0.f;
+      Bg[kk][r] = k < K ? Be0[size_t(bn) * K + k] : 0.f;
+      if (DUAL) Bu[kk][r] = k < K ? Be1[size_t(bn) * K + k] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < TK; ++kk) {
+      float a[4], bg[4], bu[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = As[kk][ty * 4 + i];
+        bg[i] = Bg[kk][tx * 4 + i];
+        bu[i] = DUAL ? Bu[kk][tx * 4 + i] : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          g[i][j] = fmaf(a[i], bg[j], g[i][j]);
+          if (DUAL) u[i][j] = fmaf(a[i], bu[j], u[i][j]);
+        }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = row0 + ty * 4 + i, col = n0 + tx * 4 + j;
+      if (row < row1 && col < N) {
+        float v = g[i][j];
+        if (DUAL) v = v / (1.0f + expf(-v)) * u[i][j];
+        C[size_t(row) * N + col] = v;
+      }
+    }
+}
+
+template <int BM, int BN1, int WM, int WN1, int BN2, int WN2, bool FP8>
+void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const int32_t* offsets,
+                      int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
+                      const float* s_gate, const float* s_up, const float* s_down, void* ys,
+                      const FfnWs& ws, hipStream_t s) {
+  const int H = c.hidden, I = c.inter_local;
+  const int max_mt = rows_capacity / BM + n_experts;
+  hipLaunchKernelGGL(ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
+                     rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles);
+  const int nt1 = (I + BN1 - 1) / BN1, nt2 = (H + BN2 - 1) / BN2;
+  auto k1 = ffn_gemm_kernel<BM, BN1, WM, WN1, true, FP8>;
+  auto k2 = ffn_gemm_kernel<BM, BN2, WM, WN2, false, FP8>;
+  constexpr int lds1 = 2 * (BM + 2 * BN1) * 8 * 16, lds2 = 2 * (BM + BN2) * 8 * 16;
+  static bool configured = false;   // LDS above 64 KB must be opted into, once per kernel
+  if (!configured) {
+    hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, lds1);
+    hipFuncSetAttribute(reinterpret_cast<const void*>(k2),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
+    configured = true;
+  }
+  hipLaunchKernelGGL(k1, dim3(size_t(max_mt) * nt1), dim3(256), lds1, s,
+                     static_cast<const uint16_t*>(xs), w_gate, w_up, s_gate, s_up,
+                     static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
+  hipLaunchKernelGGL(k2, dim3(size_t(max_mt) * nt2), dim3(256), lds2, s,
+                     static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr, s_down,
+                     (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
+}
+
+}  // namespace
+
+hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
+                             const int32_t* offsets, int rows_capacity, const void* w_gate,
+                             const void* w_up, const void* w_down, const float* s_gate,
+                             const float* s_up, const float* s_down, void* ys, const FfnWs& ws,
+                             hipStream_t s) {
+  const int H = c.hidden, I = c.inter_local;
+  if (c.act_dtype == MOE_F32) {
+    const int BM = 64;
+    const int max_mt = rows_capacity / BM + n_experts;
+    hipLaunchKernelGGL(ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
+                       rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles);
+    hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3(size_t(max_mt) * ((I + 63) / 64)), dim3(256), 0,
+                       s, static_cast<const float*>(xs), static_cast<const float*>(w_gate),
+                       static_cast<const float*>(w_up), static_cast<float*>(ws.hmid), I, H,
+                       ws.tiles);
+    hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(size_t(max_mt) * ((H + 63) / 64)), dim3(256), 0,
+                       s, static_cast<const float*>(ws.hmid), static_cast<const float*>(w_down),
+                       nullptr, static_cast<float*>(ys), H, I, ws.tiles);
+    return hipGetLastError();
+  }
+  // rows per expert can only be bounded from above on the host; pick the M
+  // tile from that bound (decode batches get the short tiles)
+  const int avg = rows_capacity / n_experts;
+  const bool fp8 = c.weight_dtype == MOE_FP8_E4M3_B128;
+#define MOE_FFN_ARGS c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, s_gate, s_up, s_down, ys, ws, s
+  if (avg <= 32) {
+    if (fp8) launch_mfma_pair<32, 128, 32, 32, 256, 64, true>(MOE_FFN_ARGS);
+    else launch_mfma_pair<32, 128, 32, 32, 256, 64, false>(MOE_FFN_ARGS);
+  } else if (avg <= 64) {
+    if (fp8) launch_mfma_pair<64, 128, 64, 32, 256, 64, true>(MOE_FFN_ARGS);
+    else launch_mfma_pair<64, 128, 64, 32, 256, 64, false>(MOE_FFN_ARGS);
+  } else {
+    if (fp8) launch_mfma_pair<128, 64, 64, 32, 128, 64, true>(MOE_FFN_ARGS);
+    else launch_mfma_pair<128, 64, 64, 32, 128, 64, false>(MOE_FFN_ARGS);
+  }
+#undef MOE_FFN_ARGS
+  return hipGetLastError();
+}
+
+}  // namespace moe

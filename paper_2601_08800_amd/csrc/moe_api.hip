@@ -1,0 +1,187 @@
+// C entry points of libmoe: host-side validation, workspace carving, launch.
+// Validation touches no HIP API, so every error path is testable without a GPU.
+#include "moe_internal.h"
+
+namespace moe {
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int act_bytes(int dt) { return dt == MOE_F32 ? 4 : 2; }
+
+// Structural checks of the layer description (dtype support is checked apart).
+static moe_status check_config(const moe_config* c) {
+  if (!c) return MOE_ERR_INVALID_ARG;
+  if (c->hidden <= 0 || c->hidden % 8) return MOE_ERR_INVALID_ARG;
+  if (c->n_experts <= 0 || c->top_k < 1 || c->top_k > c->n_experts) return MOE_ERR_INVALID_ARG;
+  if (c->score_fn != MOE_SCORE_SOFTMAX && c->score_fn != MOE_SCORE_SIGMOID)
+    return MOE_ERR_INVALID_ARG;
+  if (c->n_groups < 1 || c->n_experts % c->n_groups) return MOE_ERR_INVALID_ARG;
+  if (c->n_groups > 1) {
+    int gs = c->n_experts / c->n_groups;
+    if (c->topk_groups < 1 || c->topk_groups > c->n_groups) return MOE_ERR_INVALID_ARG;
+    if (c->group_score_n < 1 || c->group_score_n > gs) return MOE_ERR_INVALID_ARG;
+    if (c->top_k > c->topk_groups * gs) return MOE_ERR_INVALID_ARG;
+  }
+  if (c->expert_lo < 0 || c->expert_hi > c->n_experts || c->expert_lo >= c->expert_hi)
+    return MOE_ERR_INVALID_ARG;
+  if (c->inter_local <= 0 || c->inter_local % 8) return MOE_ERR_INVALID_ARG;
+  if (!(c->routed_scale == c->routed_scale)) return MOE_ERR_INVALID_ARG;  // NaN
+  // dtypes
+  if (c->act_dtype != MOE_F32 && c->act_dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  bool ok = (c->act_dtype == MOE_F32 && c->weight_dtype == MOE_F32) ||
+            (c->act_dtype == MOE_BF16 &&
+             (c->weight_dtype == MOE_BF16 || c->weight_dtype == MOE_FP8_E4M3_B128));
+  if (!ok) return MOE_ERR_UNSUPPORTED;
+  if (c->weight_dtype == MOE_FP8_E4M3_B128 && (c->inter_local % 128 || c->hidden % 128))
+    return MOE_ERR_UNSUPPORTED;
+  // kernel limits
+  if (c->top_k > 32 || c->n_experts > 512 || c->n_groups > 64) return MOE_ERR_UNSUPPORTED;
+  return MOE_OK;
+}
+
+RouteWs carve_route(void* ws, int T, int E) {
+  RouteWs r;
+  char* p = static_cast<char*>(ws);
+  size_t off = 0;
+  r.counters = reinterpret_cast<int32_t*>(p + off); off += kRouteCounterBytes;
+  r.logits = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * E * 4);
+  r.xnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * 4);
+  r.wnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(E) * 4);
+  r.recheck = reinterpret_cast<int32_t*>(p + off);  off += align_up(size_t(T) * 4);
+  r.bytes = off;
+  return r;
+}
+
+DispatchWs carve_dispatch(void* ws, int T, int k, int E_loc) {
+  DispatchWs d;
+  size_t A = size_t(T) * k;
+  d.n_blocks = int((A + kDispatchChunk - 1) / kDispatchChunk);
+  d.block_hist = static_cast<int32_t*>(ws);
+  d.bytes = align_up(size_t(d.n_blocks) * E_loc * 4);
+  return d;
+}
+
+FfnWs carve_ffn(void* ws, int rows_capacity, int n_experts, int I_loc, int abytes) {
+  FfnWs f;
+  char* p = static_cast<char*>(ws);
+  f.max_tiles = rows_capacity / kMaxTileRows + n_experts + 1;
+  size_t off = 0;
+  f.tiles = reinterpret_cast<int32_t*>(p + off); off += align_up(size_t(1 + 3 * f.max_tiles) * 4 + 12);
+  f.hmid = p + off;                              off += align_up(size_t(rows_capacity) * I_loc * abytes);
+  f.bytes = off;
+  return f;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+const char* moe_status_string(moe_status s) {
+  switch (s) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_INVALID_ARG: return "invalid argument";
+    case MOE_ERR_UNSUPPORTED: return "unsupported dtype or shape";
+    case MOE_ERR_WORKSPACE: return "workspace too small";
+    case MOE_ERR_DEVICE: return "device launch failed";
+  }
+  return "unknown status";
+}
+
+size_t moe_workspace_bytes(const moe_config* cfg, int32_t T) {
+  if (check_config(cfg) != MOE_OK || T < 0) return 0;
+  if (T == 0) return 256;
+  int k = cfg->top_k;
+  size_t r = carve_route(nullptr, T, cfg->n_experts).bytes;
+  size_t d = carve_dispatch(nullptr, T, k, cfg->expert_hi - cfg->expert_lo).bytes;
+  // the FFN is called with at most T*k rows and at most n_experts experts
+  size_t f = carve_ffn(nullptr, T * k, cfg->n_experts, cfg->inter_local,
+                       act_bytes(cfg->act_dtype)).bytes;
+  size_t m = r > d ? r : d;
+  return m > f ? m : f;
+}
+
+moe_status moe_route(const moe_config* cfg, int32_t T, const void* x, const void* gate_w,
+                     const float* logit_bias, const float* select_bias,
+                     const float* logits_in, int32_t* topk_ids, float* topk_w, void* ws,
+                     size_t ws_bytes, void* stream) {
+  moe_status st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (T < 0) return MOE_ERR_INVALID_ARG;
+  if (T == 0) return MOE_OK;
+  if (size_t(T) * cfg->n_experts > (size_t(1) << 31) - 1) return MOE_ERR_UNSUPPORTED;
+  if (!topk_ids || !topk_w || !ws) return MOE_ERR_INVALID_ARG;
+  if (!logits_in && (!x || !gate_w)) return MOE_ERR_INVALID_ARG;
+  const void* ptrs[] = {x, gate_w, logit_bias, select_bias, logits_in, topk_ids, topk_w, ws};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+  RouteWs r = carve_route(ws, T, cfg->n_experts);
+  if (ws_bytes < r.bytes) return MOE_ERR_WORKSPACE;
+  hipError_t e = launch_route(*cfg, T, x, gate_w, logit_bias, select_bias, logits_in, topk_ids,
+                              topk_w, r, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
+}
+
+moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
+                        const int32_t* topk_ids, int32_t* counts, int32_t* offsets,
+                        int32_t* perm, int32_t* inv, void* xs, void* ws, size_t ws_bytes,
+                        void* stream) {
+  moe_status st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (T < 0) return MOE_ERR_INVALID_ARG;
+  if (T == 0) return MOE_OK;
+  if (size_t(T) * cfg->top_k > (size_t(1) << 30)) return MOE_ERR_UNSUPPORTED;
+  if (!x || !topk_ids || !counts || !offsets || !perm || !inv || !xs || !ws)
+    return MOE_ERR_INVALID_ARG;
+  const void* ptrs[] = {x, topk_ids, counts, offsets, perm, inv, xs, ws};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return MOE_ERR_INVALID_ARG;
+  DispatchWs d = carve_dispatch(ws, T, cfg->top_k, cfg->expert_hi - cfg->expert_lo);
+  if (ws_bytes < d.bytes) return MOE_ERR_WORKSPACE;
+  hipError_t e = launch_dispatch(*cfg, T, x, topk_ids, counts, offsets, perm, inv, xs, d,
+                                 static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
+}
+
+moe_status moe_expert_ffn(const moe_config* cfg, int32_t n_experts_here, const void* xs,
+                          const int32_t* offsets, int32_t rows_capacity, const void* w_gate,
+                          const void* w_up, const void* w_down, const float* s_gate,
+                          const float* s_up, const float* s_down, void* ys, void* ws,
+                          size_t ws_bytes, void* stream) {
+  moe_status st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (n_experts_here < 1 || n_experts_here > cfg->n_experts || rows_capacity < 0)
+    return MOE_ERR_INVALID_ARG;
+  if (rows_capacity == 0) return MOE_OK;
+  if (!xs || !offsets || !w_gate || !w_up || !w_down || !ys || !ws) return MOE_ERR_INVALID_ARG;
+  bool fp8 = cfg->weight_dtype == MOE_FP8_E4M3_B128;
+  if (fp8 && (!s_gate || !s_up || !s_down)) return MOE_ERR_INVALID_ARG;
+  const void* ptrs[] = {xs, offsets, w_gate, w_up, w_down, s_gate, s_up, s_down, ys, ws};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+  FfnWs f = carve_ffn(ws, rows_capacity, n_experts_here, cfg->inter_local,
+                      act_bytes(cfg->act_dtype));
+  if (ws_bytes < f.bytes) return MOE_ERR_WORKSPACE;
+  hipError_t e = launch_expert_ffn(*cfg, n_experts_here, xs, offsets, rows_capacity, w_gate,
+                                   w_up, w_down, s_gate, s_up, s_down, ys, f,
+                                   static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
+}
+
+moe_status moe_combine(const moe_config* cfg, int32_t T, const void* ys, const int32_t* inv,
+                       const float* topk_w, const void* shared_ys, float* out, void* stream) {
+  moe_status st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (T < 0) return MOE_ERR_INVALID_ARG;
+  if (T == 0) return MOE_OK;
+  if (!ys || !inv || !topk_w || !out) return MOE_ERR_INVALID_ARG;
+  const void* ptrs[] = {ys, inv, topk_w, shared_ys, out};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
+  hipError_t e = launch_combine(*cfg, T, ys, inv, topk_w, shared_ys, out,
+                                static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
+}
+
+}  // extern "C"

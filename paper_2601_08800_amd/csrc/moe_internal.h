@@ -1,0 +1,71 @@
+// Internal declarations shared by the translation units of libmoe.
+// Host-side launch wrappers live next to their kernels; the C entry points in
+// moe_api.cpp validate arguments and carve the workspace.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+constexpr int kWave = 64;
+
+// ---- workspace carving (all sizes in bytes, 256-byte aligned pieces) ------
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// route
+constexpr int kRouteCounterBytes = 256;       // [0]=tokens re-scored in fp64
+constexpr int kGateChainSteps = 2;            // K-steps of 64 per fp32 accumulation chain
+struct RouteWs {
+  int32_t* counters;   // [64]
+  float* logits;       // [T,E] fast logits (fp32)
+  float* xnorm2;       // [T] sum of squares of the token row
+  float* wnorm2;       // [E] sum of squares of the gate row
+  int32_t* recheck;    // [T] token ids to re-score (bit 30 set: all experts)
+  size_t bytes;
+};
+RouteWs carve_route(void* ws, int T, int E);
+
+// dispatch
+constexpr int kDispatchChunk = 1024;          // assignments per histogram block
+struct DispatchWs {
+  int32_t* block_hist; // [n_blocks, E_loc] -> after the scan: start position of
+                       // the block's first assignment of each expert
+  int n_blocks;
+  size_t bytes;
+};
+DispatchWs carve_dispatch(void* ws, int T, int k, int E_loc);
+
+// expert FFN
+constexpr int kMaxTileRows = 32;              // smallest M tile any FFN kernel uses
+struct FfnWs {
+  int32_t* tiles;      // [0]=number of M tiles, then (expert,row0,row1) triples
+  void* hmid;          // [rows_capacity, I_loc] act dtype
+  int max_tiles;
+  size_t bytes;
+};
+FfnWs carve_ffn(void* ws, int rows_capacity, int n_experts, int I_loc, int act_bytes);
+
+// ---- launchers (return hipGetLastError() of their launches) ---------------
+hipError_t launch_route(const moe_config& c, int T, const void* x, const void* gate_w,
+                        const float* logit_bias, const float* select_bias,
+                        const float* logits_in, int32_t* ids, float* w, const RouteWs& ws,
+                        hipStream_t s);
+
+hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int32_t* ids,
+                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
+                           void* xs, const DispatchWs& ws, hipStream_t s);
+
+hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
+                             const int32_t* offsets, int rows_capacity, const void* w_gate,
+                             const void* w_up, const void* w_down, const float* s_gate,
+                             const float* s_up, const float* s_down, void* ys,
+                             const FfnWs& ws, hipStream_t s);
+
+hipError_t launch_combine(const moe_config& c, int T, const void* ys, const int32_t* inv,
+                          const float* w, const void* shared_ys, float* out, hipStream_t s);
+
+}  // namespace moe

@@ -1,0 +1,635 @@
+// Route: gate scoring and top-k selection (Sec. III-B-2: each token goes to
+// its top-k activated experts; Alg. 2: the expert map is computed from the
+// local hidden states).
+//
+// The selected ids must be those of exact arithmetic on the stored inputs,
+// whatever the summation order.  Three stages make that cheap:
+//   1. gate GEMM   bf16 MFMA 32x32x16, fp32 accumulation in short chains that
+//                  are flushed into fp64 sums; also the squared row norms
+//   2. select      one wavefront per token: keys, group limit, top-k by
+//                  shuffle arg-max, and an interval test: every comparison
+//                  the selection relied on must hold for ANY keys within the
+//                  error bound of stage 1; tokens that fail are listed
+//   3. re-score    one workgroup per listed token: the experts whose key
+//                  interval reaches the selection get an fp64 dot product and
+//                  the selection is redone in fp64
+// Error model of stage 1 for a chain of n bf16 products (exact in fp32) added
+// in fp32: every addition is off by at most one ulp of the running sum, so
+// |error| <= 2n * 2^-24 * sum|x_h w_h| <= 2n * 2^-24 * |x|_2 |w|_2.
+#include <limits.h>
+
+#include "moe_internal.h"
+
+namespace moe {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr float kUlp = 5.9604645e-8f;   // 2^-24
+
+// ------------------------------------------------------------------ helpers
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_max(T v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    T o = __shfl_xor(v, off);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T wave_min(T v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    T o = __shfl_xor(v, off);
+    v = o < v ? o : v;
+  }
+  return v;
+}
+
+// Largest value over the wave, ties to the lowest index; idx == INT_MAX marks
+// "no candidate".  Result is the same in every lane.
+template <typename T>
+__device__ __forceinline__ void wave_argmax(T& v, int& idx) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    T ov = __shfl_xor(v, off);
+    int oi = __shfl_xor(idx, off);
+    bool take = (oi != INT_MAX) && (idx == INT_MAX || ov > v || (ov == v && oi < idx));
+    if (take) { v = ov; idx = oi; }
+  }
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) {
+  return __uint_as_float(hi16 << 16);
+}
+
+// fp64 dot product of one token row with one gate row, one wavefront, fixed
+// order (lane-strided partial sums, then a butterfly): exact products, fp64 sums.
+template <bool BF16>
+__device__ __forceinline__ double wave_dot64(const void* xrow, const void* wrow, int H, int lane) {
+  double acc = 0.0;
+  if (BF16) {
+    const uint4* xa = static_cast<const uint4*>(xrow);
+    const uint4* wa = static_cast<const uint4*>(wrow);
+    for (int c = lane; c < H / 8; c += 64) {
+      const uint4 a = xa[c], b = wa[c];
+      const uint32_t av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        acc = fma((double)bf16_bits_to_f32(av[i] & 0xffffu), (double)bf16_bits_to_f32(bv[i] & 0xffffu), acc);
+        acc = fma((double)bf16_bits_to_f32(av[i] >> 16), (double)bf16_bits_to_f32(bv[i] >> 16), acc);
+      }
+    }
+  } else {
+    const float4* xa = static_cast<const float4*>(xrow);
+    const float4* wa = static_cast<const float4*>(wrow);
+    for (int c = lane; c < H / 4; c += 64) {
+      const float4 a = xa[c], b = wa[c];
+      acc = fma((double)a.x, (double)b.x, acc);
+      acc = fma((double)a.y, (double)b.y, acc);
+      acc = fma((double)a.z, (double)b.z, acc);
+      acc = fma((double)a.w, (double)b.w, acc);
+    }
+  }
+  return wave_sum(acc);
+}
+
+// ------------------------------------------------- stage 0: gate row norms
+// One wavefront per gate row: wnorm2[e] = sum_h w[e,h]^2.  Also clears the
+// re-score counter (a fill kernel rather than a memset, so the call can be
+// captured in a graph).
+template <bool BF16>
+__global__ __launch_bounds__(256) void gate_wnorm_kernel(const void* __restrict__ gate_w, int E,
+                                                        int H, float* __restrict__ wnorm2,
+                                                        int32_t* __restrict__ counters) {
+  if (blockIdx.x == 0 && threadIdx.x < 64) counters[threadIdx.x] = 0;
+  if (!gate_w) return;
+  const int lane = threadIdx.x & 63;
+  const int e = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (e >= E) return;
+  const size_t rb = size_t(e) * H * (BF16 ? 2 : 4);
+  const char* row = static_cast<const char*>(gate_w) + rb;
+  const double s = wave_dot64<BF16>(row, row, H, lane);
+  if (lane == 0) wnorm2[e] = (float)(s * (1.0 + 1e-6));
+}
+
+// ------------------------------------- stage 1 (fp32 inputs): fp64 VALU gate
+// One workgroup per token; each wavefront takes every 4th expert.
+__global__ __launch_bounds__(256) void gate_f64_kernel(const float* __restrict__ x,
+                                                      const float* __restrict__ gate_w, int T,
+                                                      int H, int E, float* __restrict__ logits,
+                                                      float* __restrict__ xnorm2) {
+  const int t = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float* xr = x + size_t(t) * H;
+  for (int e = wave; e < E; e += 4) {
+    const double z = wave_dot64<false>(xr, gate_w + size_t(e) * H, H, lane);
+    if (lane == 0) logits[size_t(t) * E + e] = (float)z;
+  }
+  if (wave == 0) {
+    const double s = wave_dot64<false>(xr, xr, H, lane);
+    if (lane == 0) xnorm2[t] = (float)(s * (1.0 + 1e-6));
+  }
+}
+
+// ------------------------------------------ stage 1 (bf16): MFMA gate GEMM
+// Block tile 64 tokens x 128 experts, K step 64, 4 wavefronts as 2 (M) x 2 (N),
+// each 32 x 64 = two 32x32 MFMA tiles.  LDS tiles are [row][8 pieces of 16 B]
+// with the piece index XOR-ed by (row & 7) so that the 16-byte operand reads of
+// 8 consecutive rows fall in different banks.
+constexpr int GBM = 64, GBN = 128, GBK = 64;
+
+__device__ __forceinline__ int swz(int row, int piece) { return row * 8 + (piece ^ (row & 7)); }
+
+template <int CHAIN_STEPS>
+__global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restrict__ x,
+                                                       const uint16_t* __restrict__ gate_w, int T,
+                                                       int H, int E, float* __restrict__ logits,
+                                                       float* __restrict__ xnorm2) {
+  __shared__ uint4 As[2][GBM * 8];
+  __shared__ uint4 Bs[2][GBN * 8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN;
+  const int ksteps = (H + GBK - 1) / GBK;
+
+  // global -> register staging: A 2 pieces / thread, B 4 pieces / thread
+  const int lrow = tid >> 3, lpiece = tid & 7;
+  uint4 ra[2], rb[4];
+  float xsq[2] = {0.f, 0.f};
+  auto gload = [&](int ks) {
+    const int kcol = ks * GBK + lpiece * 8;
+    const bool kin = kcol < H;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int r = m0 + lrow + 32 * i;
+      r = r < T ? r : T - 1;
+      ra[i] = kin ? *reinterpret_cast<const uint4*>(x + size_t(r) * H + kcol) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int r = n0 + lrow + 32 * i;
+      r = r < E ? r : E - 1;
+      rb[i] = kin ? *reinterpret_cast<const uint4*>(gate_w + size_t(r) * H + kcol) : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      As[buf][swz(lrow + 32 * i, lpiece)] = ra[i];
+      const uint32_t v[4] = {ra[i].x, ra[i].y, ra[i].z, ra[i].w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float lo = bf16_bits_to_f32(v[q] & 0xffffu), hi = bf16_bits_to_f32(v[q] >> 16);
+        xsq[i] = fmaf(lo, lo, xsq[i]);
+        xsq[i] = fmaf(hi, hi, xsq[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Bs[buf][swz(lrow + 32 * i, lpiece)] = rb[i];
+  };
+
+  f32x16 acc[2];
+  double dsum[2][16];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc[j][i] = 0.f; dsum[j][i] = 0.0; }
+
+  gload(0);
+  lstore(0);
+  __syncthreads();
+  for (int ks = 0; ks < ksteps; ++ks) {
+    const int buf = ks & 1;
+    if (ks + 1 < ksteps) gload(ks + 1);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int piece = kk * 2 + (lane >> 5);
+      const uint4 av = As[buf][swz(wm * 32 + (lane & 31), piece)];
+      const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const uint4 bv = Bs[buf][swz(wn * 64 + j * 32 + (lane & 31), piece)];
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[j], 0, 0, 0);
+      }
+    }
+    if ((ks + 1) % CHAIN_STEPS == 0 || ks + 1 == ksteps) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { dsum[j][i] += (double)acc[j][i]; acc[j][i] = 0.f; }
+    }
+    if (ks + 1 < ksteps) lstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // D layout of the 32x32 MFMA: lane l, register i -> row (i/4)*8 + (l/32)*4 + i%4, col l%32
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = m0 + wm * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+      if (row < T && col < E) logits[size_t(row) * E + col] = (float)dsum[j][i];
+    }
+  }
+  // squared row norms: the 8 threads with equal lrow hold one row's pieces
+  if (blockIdx.y == 0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      float s = xsq[i];
+      s += __shfl_xor(s, 1);
+      s += __shfl_xor(s, 2);
+      s += __shfl_xor(s, 4);
+      const int r = m0 + lrow + 32 * i;
+      if (lpiece == 0 && r < T) xnorm2[r] = s * 1.001f;
+    }
+  }
+}
+
+// ----------------------------------------------------------- stage 2: select
+struct SelCfg {
+  int E, k, score_fn, renormalize, G, Kg, gn;
+  float scale;
+  float chain_err;   // 2n * 2^-24 of the gate accumulation (0 when logits are given)
+  int have_norms;
+};
+
+// Per-lane view of one token's experts: expert e = slot*64 + lane.
+template <typename FT, int EPL>
+struct Keys {
+  FT key[EPL];   // selection key
+  FT eps[EPL];   // bound on |key - exact key|
+  FT sc[EPL];    // value the weight is made of: logit (softmax) or sigmoid score
+};
+
+template <typename FT, int EPL>
+struct Picks {
+  int id;        // lane j < k: j-th pick
+  FT sc;         // its logit / score
+  FT low;        // smallest lower bound of a picked key
+  bool certain;  // every comparison held with the error intervals apart
+  bool groups_certain;
+  uint32_t elig; // bit per slot: expert may be selected (valid and in a kept group)
+};
+
+// Fast keys of token t from the stage-1 logits.
+template <int EPL>
+__device__ __forceinline__ void fast_keys(const SelCfg& c, const float* __restrict__ logits_row,
+                                          const float* __restrict__ logit_bias,
+                                          const float* __restrict__ select_bias, float xn,
+                                          const float* __restrict__ wnorm2, int lane,
+                                          Keys<float, EPL>& K) {
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int e = i * 64 + lane;
+    float key = -INFINITY, eps = 0.f, sc = 0.f;
+    if (e < c.E) {
+      float z = logits_row[e];
+      float ez = 0.f;
+      if (c.have_norms) ez = c.chain_err * xn * sqrtf(wnorm2[e]) * 1.001f + 2.f * kUlp * fabsf(z);
+      if (logit_bias) {
+        z += logit_bias[e];
+        ez += kUlp * fabsf(z);
+      }
+      if (c.score_fn == MOE_SCORE_SOFTMAX) {
+        key = z; eps = ez; sc = z;
+      } else {
+        const float s = 1.0f / (1.0f + expf(-z));
+        const float sb = select_bias ? select_bias[e] : 0.f;
+        key = s + sb;
+        sc = s;
+        // |sigmoid(z+d)-sigmoid(z)| <= s(1-s)|d| + d^2/16 ; fp32 evaluation of
+        // the sigmoid and of the bias add is good to a few ulp of 1+|sb|
+        eps = ez * (s * (1.f - s) + ez + 16.f * kUlp) + 16.f * kUlp * (1.f + fabsf(sb));
+      }
+    }
+    K.key[i] = key; K.eps[i] = eps; K.sc[i] = sc;
+  }
+}
+
+// Group limit and top-k over one wavefront.  Ties go to the lowest index.
+template <typename FT, int EPL>
+__device__ __forceinline__ void select_topk(const SelCfg& c, const Keys<FT, EPL>& K, int lane,
+                                            Picks<FT, EPL>& P) {
+  uint32_t elig = 0;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i)
+    if (i * 64 + lane < c.E) elig |= 1u << i;
+  P.certain = true;
+  P.groups_certain = true;
+
+  if (c.G > 1) {
+    const int gs = c.E / c.G;
+    FT gsum = 0, gerr = 0;        // lane g holds group g
+    for (int g = 0; g < c.G; ++g) {
+      uint32_t taken = 0;
+      FT sum = 0, me = 0;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        const int e = i * 64 + lane;
+        if (e < c.E && e / gs == g) me = K.eps[i] > me ? K.eps[i] : me;
+      }
+      me = wave_max(me);
+      for (int r = 0; r < c.gn; ++r) {
+        FT v = 0; int idx = INT_MAX;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+          const int e = i * 64 + lane;
+          if (e < c.E && e / gs == g && !(taken >> i & 1) && (idx == INT_MAX || K.key[i] > v)) {
+            v = K.key[i]; idx = e;
+          }
+        }
+        wave_argmax(v, idx);
+        sum += v;
+        if ((idx & 63) == lane) taken |= 1u << (idx >> 6);
+      }
+      if (lane == g) { gsum = sum; gerr = me * (FT)c.gn; }
+    }
+    uint64_t kept = 0;
+    FT low = INFINITY;
+    for (int r = 0; r < c.Kg; ++r) {
+      FT v = gsum; int idx = (lane < c.G && !(kept >> lane & 1)) ? lane : INT_MAX;
+      wave_argmax(v, idx);
+      kept |= uint64_t(1) << idx;
+      const FT lo = __shfl(gsum - gerr, idx);
+      low = lo < low ? lo : low;
+    }
+    FT hi = (lane < c.G && !(kept >> lane & 1)) ? gsum + gerr : -INFINITY;
+    hi = wave_max(hi);
+    if (!(low > hi)) P.groups_certain = false;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const int e = i * 64 + lane;
+      if (e < c.E && !(kept >> (e / gs) & 1)) elig &= ~(1u << i);
+    }
+  }
+  P.elig = elig;
+
+  uint32_t taken = 0;
+  FT prev_lo = INFINITY, low = INFINITY;
+  P.id = -1; P.sc = 0;
+  for (int j = 0; j < c.k; ++j) {
+    FT v = 0; int idx = INT_MAX;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      if ((elig >> i & 1) && !(taken >> i & 1) && (idx == INT_MAX || K.key[i] > v)) {
+        v = K.key[i]; idx = i * 64 + lane;
+      }
+    }
+    wave_argmax(v, idx);
+    const int owner = idx & 63, slot = idx >> 6;
+    FT oe = 0, os = 0;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+      if (i == slot) { oe = K.eps[i]; os = K.sc[i]; }
+    oe = __shfl(oe, owner);
+    os = __shfl(os, owner);
+    if (lane == owner) taken |= 1u << slot;
+    if (lane == j) { P.id = idx; P.sc = os; }
+    if (!(prev_lo > v + oe) && j > 0) P.certain = false;
+    prev_lo = v - oe;
+    low = prev_lo < low ? prev_lo : low;
+  }
+  FT hi = -INFINITY;
+  bool any = false;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i)
+    if ((elig >> i & 1) && !(taken >> i & 1)) {
+      const FT h = K.key[i] + K.eps[i];
+      hi = (!any || h > hi) ? h : hi;
+      any = true;
+    }
+  const bool some = __ballot(any) != 0;
+  hi = wave_max(any ? hi : (FT)-INFINITY);
+  if (some && !(prev_lo > hi)) P.certain = false;
+  if (!P.groups_certain) P.certain = false;
+  P.low = low;
+}
+
+// Weights of the picked experts; lane j < k returns w[t,j].
+template <typename FT, int EPL>
+__device__ __forceinline__ FT pick_weight(const SelCfg& c, const Keys<FT, EPL>& K,
+                                          const Picks<FT, EPL>& P, int lane) {
+  const bool mine = lane < c.k;
+  FT num, den;
+  if (c.score_fn == MOE_SCORE_SOFTMAX) {
+    if (c.renormalize) {
+      const FT m = wave_max(mine ? P.sc : (FT)-INFINITY);
+      num = mine ? (FT)exp((FT)(P.sc - m)) : (FT)0;
+      den = wave_sum(num);
+    } else {
+      FT m = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i)
+        if (i * 64 + lane < c.E) m = K.sc[i] > m ? K.sc[i] : m;
+      m = wave_max(m);
+      FT s = 0;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i)
+        if (i * 64 + lane < c.E) s += (FT)exp((FT)(K.sc[i] - m));
+      den = wave_sum(s);
+      num = mine ? (FT)exp((FT)(P.sc - m)) : (FT)0;
+    }
+  } else {
+    num = mine ? P.sc : (FT)0;
+    den = c.renormalize ? wave_sum(num) : (FT)1;
+  }
+  return num / den * (FT)c.scale;
+}
+
+template <int EPL>
+__global__ __launch_bounds__(256) void route_select_kernel(
+    SelCfg c, int T, const float* __restrict__ logits, const float* __restrict__ logit_bias,
+    const float* __restrict__ select_bias, const float* __restrict__ xnorm2,
+    const float* __restrict__ wnorm2, int32_t* __restrict__ ids, float* __restrict__ w,
+    int32_t* __restrict__ counters, int32_t* __restrict__ recheck) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  Keys<float, EPL> K;
+  const float xn = c.have_norms ? sqrtf(xnorm2[t]) : 0.f;
+  fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
+  Picks<float, EPL> P;
+  select_topk<float, EPL>(c, K, lane, P);
+  if (P.certain) {
+    const float wt = pick_weight<float, EPL>(c, K, P, lane);
+    if (lane < c.k) {
+      ids[size_t(t) * c.k + lane] = P.id;
+      w[size_t(t) * c.k + lane] = wt;
+    }
+  } else if (lane == 0) {
+    // order of the list is irrelevant: every listed token is re-scored on its own
+    const int slot = atomicAdd(&counters[0], 1);
+    recheck[slot] = t;
+  }
+}
+
+// --------------------------------------------------------- stage 3: re-score
+template <int EPL, bool BF16>
+__global__ __launch_bounds__(256) void route_recheck_kernel(
+    SelCfg c, int H, const void* __restrict__ x, const void* __restrict__ gate_w,
+    const float* __restrict__ logits_in, const float* __restrict__ logits,
+    const float* __restrict__ logit_bias, const float* __restrict__ select_bias,
+    const float* __restrict__ xnorm2, const float* __restrict__ wnorm2, int32_t* __restrict__ ids,
+    float* __restrict__ w, const int32_t* __restrict__ counters,
+    const int32_t* __restrict__ recheck) {
+  __shared__ int xlist[512];
+  __shared__ double zx[512];
+  __shared__ int n_x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n_list = counters[0];
+  for (int li = blockIdx.x; li < n_list; li += gridDim.x) {
+    const int t = recheck[li];
+    Keys<float, EPL> K;
+    Picks<float, EPL> P;
+    uint32_t inx = 0;
+    if (wave == 0) {
+      const float xn = c.have_norms ? sqrtf(xnorm2[t]) : 0.f;
+      fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
+      select_topk<float, EPL>(c, K, lane, P);
+      // experts whose exact key could reach the selection; all of them when the
+      // group cut itself is in doubt
+      int n = 0;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        const int e = i * 64 + lane;
+        bool in = e < c.E;
+        if (P.groups_certain) in = (P.elig >> i & 1) && (K.key[i] + K.eps[i] >= P.low);
+        const uint64_t m = __ballot(in);
+        if (in) {
+          xlist[n + __popcll(m & ((uint64_t(1) << lane) - 1))] = e;
+          inx |= 1u << i;
+        }
+        n += __popcll(m);
+      }
+      if (lane == 0) n_x = n;
+    }
+    __syncthreads();
+    const int n = n_x;
+    for (int q = wave; q < n; q += 4) {
+      const int e = xlist[q];
+      double z;
+      if (logits_in) {
+        z = (double)logits_in[size_t(t) * c.E + e];
+      } else {
+        const size_t eb = BF16 ? 2 : 4;
+        z = wave_dot64<BF16>(static_cast<const char*>(x) + size_t(t) * H * eb,
+                             static_cast<const char*>(gate_w) + size_t(e) * H * eb, H, lane);
+      }
+      if (logit_bias) z += (double)logit_bias[e];
+      if (lane == 0) zx[e] = z;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      Keys<double, EPL> D;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        const int e = i * 64 + lane;
+        D.key[i] = (double)K.key[i];
+        D.sc[i] = (double)K.sc[i];
+        D.eps[i] = 0.0;
+        if (inx >> i & 1) {
+          const double z = zx[e];
+          if (c.score_fn == MOE_SCORE_SOFTMAX) {
+            D.key[i] = z; D.sc[i] = z;
+          } else {
+            const double s = 1.0 / (1.0 + exp(-z));
+            D.sc[i] = s;
+            D.key[i] = s + (select_bias ? (double)select_bias[e] : 0.0);
+          }
+        }
+      }
+      Picks<double, EPL> Q;
+      select_topk<double, EPL>(c, D, lane, Q);
+      const double wt = pick_weight<double, EPL>(c, D, Q, lane);
+      if (lane < c.k) {
+        ids[size_t(t) * c.k + lane] = Q.id;
+        w[size_t(t) * c.k + lane] = (float)wt;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <int EPL>
+void launch_select_and_recheck(const SelCfg& sc, const moe_config& c, int T, const void* x,
+                               const void* gate_w, const float* logit_bias,
+                               const float* select_bias, const float* logits_in,
+                               const float* logits, int32_t* ids, float* w, const RouteWs& ws,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(route_select_kernel<EPL>, dim3((T + 3) / 4), dim3(256), 0, s, sc, T, logits,
+                     logit_bias, select_bias, ws.xnorm2, ws.wnorm2, ids, w, ws.counters,
+                     ws.recheck);
+  const int grid = T < 4096 ? T : 4096;
+  if (c.act_dtype == MOE_BF16)
+    hipLaunchKernelGGL((route_recheck_kernel<EPL, true>), dim3(grid), dim3(256), 0, s, sc,
+                       c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
+                       ws.wnorm2, ids, w, ws.counters, ws.recheck);
+  else
+    hipLaunchKernelGGL((route_recheck_kernel<EPL, false>), dim3(grid), dim3(256), 0, s, sc,
+                       c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
+                       ws.wnorm2, ids, w, ws.counters, ws.recheck);
+}
+
+}  // namespace
+
+hipError_t launch_route(const moe_config& c, int T, const void* x, const void* gate_w,
+                        const float* logit_bias, const float* select_bias,
+                        const float* logits_in, int32_t* ids, float* w, const RouteWs& ws,
+                        hipStream_t s) {
+  const int E = c.n_experts, H = c.hidden;
+  const bool bf16 = c.act_dtype == MOE_BF16;
+  const float* logits = logits_in;
+  SelCfg sc;
+  sc.E = E; sc.k = c.top_k; sc.score_fn = c.score_fn; sc.renormalize = c.renormalize;
+  sc.G = c.n_groups; sc.Kg = c.topk_groups; sc.gn = c.group_score_n; sc.scale = c.routed_scale;
+  sc.chain_err = 0.f; sc.have_norms = 0;
+  const void* gw_for_norm = logits_in ? nullptr : gate_w;
+  if (bf16)
+    hipLaunchKernelGGL(gate_wnorm_kernel<true>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm, E,
+                       H, ws.wnorm2, ws.counters);
+  else
+    hipLaunchKernelGGL(gate_wnorm_kernel<false>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm,
+                       E, H, ws.wnorm2, ws.counters);
+  if (!logits_in) {
+    logits = ws.logits;
+    sc.have_norms = 1;
+    if (bf16) {
+      const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN);
+      hipLaunchKernelGGL(gate_mfma_kernel<kGateChainSteps>, grid, dim3(256), 0, s,
+                         static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T,
+                         H, E, ws.logits, ws.xnorm2);
+      // chains of kGateChainSteps*64 products; +2 for the flush and the store
+      sc.chain_err = (2.f * kGateChainSteps * GBK + 2.f) * kUlp;
+    } else {
+      hipLaunchKernelGGL(gate_f64_kernel, dim3(T), dim3(256), 0, s, static_cast<const float*>(x),
+                         static_cast<const float*>(gate_w), T, H, E, ws.logits, ws.xnorm2);
+      // fp64 sums: the only error is the fp32 store, covered by the 2 ulp term
+      sc.chain_err = 1e-12f;
+    }
+  }
+  const int epl = (E + 63) / 64;
+  if (epl <= 1)
+    launch_select_and_recheck<1>(sc, c, T, x, gate_w, logit_bias, select_bias, logits_in, logits, ids, w, ws, s);
+  else if (epl <= 2)
+    launch_select_and_recheck<2>(sc, c, T, x, gate_w, logit_bias, select_bias, logits_in, logits, ids, w, ws, s);
+  else if (epl <= 4)
+    launch_select_and_recheck<4>(sc, c, T, x, gate_w, logit_bias, select_bias, logits_in, logits, ids, w, ws, s);
+  else
+    launch_select_and_recheck<8>(sc, c, T, x, gate_w, logit_bias, select_bias, logits_in, logits, ids, w, ws, s);
+  return hipGetLastError();
+}
+
+}  // namespace moe

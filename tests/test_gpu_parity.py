@@ -1,0 +1,193 @@
+"""HIP path vs CPU oracle through the C ABI, element by element, on small and
+scaled-down workloads that still span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from workloads import gen
+from helpers import (TOL, check_dispatch, check_routing, dev, host, inputs, make_layer,
+                     oracle_out_for_tokens, oracle_route, rel_err)
+
+pytestmark = pytest.mark.gpu
+
+SMALL = {
+    "c1": gen.CONFIGS["c1"],
+    # Qwen3-like, ragged T, several M tiles per expert for some experts
+    "qwen_small": gen.CONFIGS["c2p"].replace(name="qwen_small", T=777, H=512, E=32, k=4, I=384),
+    # EP share with skew bias
+    "ep_small": gen.CONFIGS["c3"].replace(name="ep_small", T=1500, H=256, E=64, k=8, I=256,
+                                          expert_lo=8, expert_hi=16),
+    # DeepSeek-like: sigmoid, groups, shared expert, TP slice
+    "ds_small": gen.CONFIGS["c4"].replace(name="ds_small", T=1111, H=512, E=64, k=8, I=512,
+                                          expert_lo=16, expert_hi=24),
+    # decode-like: few tokens per expert
+    "decode_small": gen.CONFIGS["c2d"].replace(name="decode_small", T=19, H=512, E=32, k=4, I=256),
+    # medium rows per expert (the 64-row M tile)
+    "mid_small": gen.CONFIGS["c2p"].replace(name="mid_small", T=100, H=256, E=16, k=8, I=128),
+    # fp8 weights, few rows per expert (short M tiles), no group limit
+    "fp8_decode_small": gen.CONFIGS["c5"].replace(name="fp8_decode_small", T=40, H=256, E=16, k=4,
+                                                  I=256, expert_lo=0, expert_hi=16, zipf_s=None,
+                                                  n_groups=1, topk_groups=1, group_score_n=0),
+    # fp8 weights, natural routing
+    "fp8_small": gen.CONFIGS["c5"].replace(name="fp8_small", T=300, H=512, E=64, k=8, I=512,
+                                           expert_lo=0, expert_hi=8, zipf_s=None),
+}
+
+
+def run_full(w):
+    d = inputs(w)
+    L = make_layer(w, d)
+    x = dev(d["x"])
+    forced = None
+    if d["forced"] is not None:
+        forced = (dev(d["forced"][0]), dev(d["forced"][1]))
+    out = L.forward(x, forced)
+    torch.cuda.synchronize()
+    return d, L, host(out)
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_layer_share_matches_oracle(name):
+    w = SMALL[name]
+    print("case", name, flush=True)
+    d, L, out = run_full(w)
+    ids_ref, w_ref, margin = oracle_route(w, d["x"], d["gate"])
+    ids, wts = host(L.topk_ids), host(L.topk_w)
+    check_routing(ids, wts, ids_ref, w_ref, margin, w.routed_scale, name)
+    check_dispatch(L, ids_ref, w, d["x"])
+    ref, parts = oracle.layer_share(d["x"], ids_ref, w_ref, w.expert_lo, w.e_hi, d["experts"],
+                                    d["shared"])
+    n = int(parts["offsets"][-1])
+    ys = oracle.decode(host(L.ys[:n])) if w.act_dtype == "bf16" else host(L.ys[:n])
+    tol = TOL[w.weight_dtype]
+    assert n == 0 or rel_err(ys, parts["ys"][:n]) <= tol
+    assert rel_err(out, ref) <= tol, rel_err(out, ref)
+
+
+def test_route_recheck_counter_and_determinism():
+    w = SMALL["qwen_small"]
+    d = inputs(w)
+    L = make_layer(w, d)
+    x = dev(d["x"])
+    L.route(x)
+    torch.cuda.synchronize()
+    n1 = int(L.ws[:4].view(torch.int32).item())
+    a = (host(L.topk_ids).copy(), host(L.topk_w).copy())
+    L.route(x)
+    torch.cuda.synchronize()
+    assert int(L.ws[:4].view(torch.int32).item()) == n1 and 0 <= n1 <= w.T
+    assert np.array_equal(a[0], host(L.topk_ids)) and np.array_equal(a[1], host(L.topk_w))
+
+
+@pytest.mark.parametrize("E,k,score,G,Kg,gn", [
+    (8, 2, "softmax", 1, 1, 0), (64, 6, "softmax", 1, 1, 0), (100, 8, "softmax", 1, 1, 0),
+    (128, 8, "softmax", 1, 1, 0), (256, 8, "sigmoid", 8, 4, 2), (256, 8, "sigmoid", 1, 1, 0),
+    (96, 4, "sigmoid", 6, 3, 1), (512, 32, "softmax", 1, 1, 0), (48, 5, "sigmoid", 4, 2, 3)])
+def test_selection_logic_on_given_logits(E, k, score, G, Kg, gn):
+    """Identical fp32 logits on both sides: the selection alone must be bit-exact."""
+    from paper_2601_08800_amd import MoELayerShare
+    from paper_2601_08800_amd.layer import config_from_workload
+    T = 513
+    rng = np.random.default_rng(E * 7 + k)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[5] = 0.25                       # a row of exact ties
+    logits[6, : E // 2] = 1.0              # partial ties
+    w = gen.CONFIGS["c2d"].replace(T=T, H=64, E=E, k=k, I=64, score_fn=score, n_groups=G,
+                                   topk_groups=Kg, group_score_n=gn, routed_scale=2.5,
+                                   select_bias_std=0.05 if score == "sigmoid" else 0.0,
+                                   logit_bias_std=0.3 if score == "softmax" else 0.0)
+    gate = gen.make_gate(w)
+    ids_ref, w_ref, margin = oracle_route(w, None, gate, logits_in=logits)
+    L = MoELayerShare(config_from_workload(w), T, gate,
+                      {"w_gate": None, "w_up": None, "w_down": None})
+    L.route(None, logits_in=dev(logits))
+    torch.cuda.synchronize()
+    ids, wts = host(L.topk_ids), host(L.topk_w)
+    assert np.array_equal(ids, ids_ref)
+    np.testing.assert_allclose(wts, w_ref, rtol=2e-5, atol=5e-6)
+
+
+def test_exact_arithmetic_gate_with_ties():
+    """Small-integer activations and gate weights: every summation order gives
+    the same logits, so ids must match exactly, deliberate ties included."""
+    from paper_2601_08800_amd import MoELayerShare
+    from paper_2601_08800_amd.layer import config_from_workload
+    T, H, E, k = 200, 192, 24, 3
+    rng = np.random.default_rng(3)
+    xi = rng.integers(-3, 4, size=(T, H)).astype(np.float32)
+    gi = rng.integers(-2, 3, size=(E, H)).astype(np.float32)
+    gi[7] = gi[2]                                             # two identical experts
+    for act in ("bf16", "f32"):
+        w = gen.CONFIGS["c2d"].replace(T=T, H=H, E=E, k=k, I=64, act_dtype=act,
+                                       weight_dtype=act)
+        x = gen.f32_to_bf16_bits(xi) if act == "bf16" else xi
+        g = gen.f32_to_bf16_bits(gi) if act == "bf16" else gi
+        gate = {"gate_w": g, "logit_bias": None, "select_bias": None}
+        ids_ref, w_ref, margin = oracle_route(w, x, gate)
+        assert (margin == 0).sum() > 0
+        L = MoELayerShare(config_from_workload(w), T, gate,
+                          {"w_gate": None, "w_up": None, "w_down": None})
+        L.route(dev(x))
+        torch.cuda.synchronize()
+        assert np.array_equal(host(L.topk_ids), ids_ref)
+        np.testing.assert_allclose(host(L.topk_w), w_ref, rtol=2e-5)
+
+
+def test_identity_experts_return_input():
+    """Skipping the MLP (ys := xs) the share returns (sum of weights) * x."""
+    for name in ("qwen_small", "c1"):
+        w = SMALL[name].replace(expert_lo=0, expert_hi=0)
+        d = inputs(w)
+        L = make_layer(w, d)
+        x = dev(d["x"])
+        L.route(x)
+        L.dispatch(x)
+        L.combine(ys=L.xs)
+        torch.cuda.synchronize()
+        xf = oracle.decode(d["x"])
+        assert int(host(L.offsets)[-1]) == w.T * w.k
+        assert rel_err(host(L.out), xf) <= (1e-6 if name == "c1" else 2e-6)
+
+
+@pytest.mark.parametrize("T,e_lo,e_hi", [(1, 0, 16), (3, 5, 6), (1025, 0, 16), (2048, 15, 16),
+                                          (64, 3, 9)])
+def test_dispatch_edge_cases(T, e_lo, e_hi):
+    w = gen.CONFIGS["c2d"].replace(T=T, H=128, E=16, k=4, I=64, expert_lo=e_lo, expert_hi=e_hi)
+    rng = np.random.default_rng(T)
+    ids = np.stack([rng.permutation(16)[:4] for _ in range(T)]).astype(np.int32)
+    if T > 100:
+        ids[:, 0] = 15                     # one very hot expert, several empty ones
+        ids[:, 1:] = np.stack([rng.permutation(5)[:3] for _ in range(T)])
+    d = {"x": gen.make_x(w), "gate": gen.make_gate(w),
+         "experts": {"w_gate": None, "w_up": None, "w_down": None}, "shared": None}
+    L = make_layer(w, d)
+    L.topk_ids = dev(ids)
+    L.dispatch(dev(d["x"]))
+    torch.cuda.synchronize()
+    check_dispatch(L, ids, w, d["x"])
+
+
+def test_tp_and_ep_additivity_on_gpu():
+    """Partial outputs of the TP slices / EP ranges add up to the full layer
+    (block matrix multiplication; experts are independent)."""
+    base = gen.CONFIGS["c2p"].replace(T=200, H=256, E=16, k=4, I=256)
+    d = inputs(base)
+    full = make_layer(base, d).forward(dev(d["x"])).clone()
+    acc = torch.zeros_like(full)
+    for r in range(2):                     # EP = 2
+        w = base.replace(expert_lo=8 * r, expert_hi=8 * r + 8)
+        acc += make_layer(w, inputs(w)).forward(dev(d["x"]))
+    torch.cuda.synchronize()
+    assert rel_err(host(acc), host(full)) <= 1e-6
+    tp = base.replace(tp=2, I=512)         # two slices of 256
+    ids_ref, w_ref, _ = oracle_route(tp, d["x"], d["gate"])
+    ref = np.zeros((tp.T, tp.H))
+    got = torch.zeros_like(full)
+    for r in range(2):
+        wr = tp.replace(tp_rank=r)
+        dr = inputs(wr)
+        got += make_layer(wr, dr).forward(dev(dr["x"]))
+        ref += oracle.layer_share(dr["x"], ids_ref, w_ref, 0, 16, dr["experts"])[0]
+    torch.cuda.synchronize()
+    assert rel_err(host(got), ref) <= TOL["bf16"]

@@ -18,6 +18,8 @@ Storage conventions of the returned numpy arrays
 from __future__ import annotations
 
 import dataclasses
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 from typing import Dict, Optional
 
@@ -138,18 +140,14 @@ def quantize_e4m3_block128(w: np.ndarray):
     """Per 128x128 block: scale = max|w|/448 (fp32), codes = e4m3(w/scale)."""
     R, C = w.shape
     nr, nc = -(-R // FP8_BLOCK), -(-C // FP8_BLOCK)
-    codes = np.empty((R, C), np.uint8)
-    scales = np.empty((nr, nc), np.float32)
-    for i in range(nr):
-        rs = slice(i * FP8_BLOCK, min(R, (i + 1) * FP8_BLOCK))
-        for j in range(nc):
-            cs = slice(j * FP8_BLOCK, min(C, (j + 1) * FP8_BLOCK))
-            blk = w[rs, cs]
-            m = np.float32(np.max(np.abs(blk)))
-            s = np.float32(m / np.float32(E4M3_MAX)) if m > 0 else np.float32(1.0)
-            scales[i, j] = s
-            codes[rs, cs] = f32_to_e4m3_codes(blk / s)
-    return codes, scales
+    pad = np.zeros((nr * FP8_BLOCK, nc * FP8_BLOCK), np.float32)
+    pad[:R, :C] = w
+    blk = pad.reshape(nr, FP8_BLOCK, nc, FP8_BLOCK)
+    m = np.abs(blk).max(axis=(1, 3)).astype(np.float32)
+    scales = np.where(m > 0, m / np.float32(E4M3_MAX), np.float32(1.0)).astype(np.float32)
+    q = (blk / scales[:, None, :, None]).astype(np.float32)
+    codes = f32_to_e4m3_codes(q.reshape(nr * FP8_BLOCK, nc * FP8_BLOCK))[:R, :C]
+    return np.ascontiguousarray(codes), scales
 
 
 def _rng(seed: int, kind: int, idx: int = 0) -> np.random.Generator:
@@ -215,14 +213,25 @@ def make_expert_weights(w: Workload, expert_ids, tp_rank: Optional[int] = None) 
         out["s_gate"] = np.empty((n, bi, bh), np.float32)
         out["s_up"] = np.empty((n, bi, bh), np.float32)
         out["s_down"] = np.empty((n, bh, bi), np.float32)
-    for i, e in enumerate(expert_ids):
-        for name, sname, kind, shape in (("w_gate", "s_gate", _K_GATE, (Il, H)),
-                                         ("w_up", "s_up", _K_UP, (Il, H)),
-                                         ("w_down", "s_down", _K_DOWN, (H, Il))):
-            q, s = _expert_matrix(w, kind, int(e), tp_rank, shape)
-            out[name][i] = q
-            if s is not None:
-                out[sname][i] = s
+    jobs = [(i, int(e), name, sname, kind, shape)
+            for i, e in enumerate(expert_ids)
+            for name, sname, kind, shape in (("w_gate", "s_gate", _K_GATE, (Il, H)),
+                                             ("w_up", "s_up", _K_UP, (Il, H)),
+                                             ("w_down", "s_down", _K_DOWN, (H, Il)))]
+
+    def run(job):
+        i, e, name, sname, kind, shape = job
+        q, s = _expert_matrix(w, kind, e, tp_rank, shape)
+        out[name][i] = q
+        if s is not None:
+            out[sname][i] = s
+
+    if len(jobs) > 3:       # independent streams: draw them on a few threads
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            list(ex.map(run, jobs))
+    else:
+        for j in jobs:
+            run(j)
     return out
 
 
