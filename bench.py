@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of one GPU's MoE-layer share: route -> dispatch -> expert FFN ->
+combine on seeded synthetic layers, one JSON line on stdout.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2p|c2d|c3|c4|c5|c1]
+
+A step is one pass of the whole path over one batch, inputs resident in HBM.
+`value` is tokens/s of the share; `roofline` prices the dominant kernel against
+MI355X's published peaks using the kernel's algorithmic flops / bytes and its
+duration measured with HIP events on the stream it runs on; `cpu_baseline` is
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_TFLOPS = {"bf16": 2500.0, "fp8": 2500.0, "f32": 157.3}   # fp8 weights run on the bf16 MFMA
+
+DESCR = {
+    "c1": "tiny fp32 layer: 64 tokens, hidden 256, 8 experts top-2, I 512",
+    "c2p": "Qwen3-30B-A3B-shaped full layer, prefill 4096 tokens: hidden 2048, 128 experts top-8, I 768, bf16",
+    "c2d": "Qwen3-30B-A3B-shaped full layer, decode 64 tokens: hidden 2048, 128 experts top-8, I 768, bf16",
+    "c3": "Qwen3-235B-A22B-shaped EP=8 share: 8192 tokens, hidden 4096, 16 of 128 experts, I 1536, bf16",
+    "c4": "DeepSeek-R1-shaped TP=2 x EP share: 16384 tokens, hidden 7168, 32 of 256 experts + shared, I 1024, bf16",
+    "c5": "DeepSeek-R1-shaped decode stress: 256 tokens, fp8-e4m3 block-128 weights, forced Zipf routing",
+}
+
+
+def algorithmic_work(w, a_loc, e_touched, tokens_local):
+    """Per step, per kernel id: (flops, bytes) the method itself must do / move."""
+    ab = 4 if w.act_dtype == "f32" else 2
+    wb = {"f32": 4, "bf16": 2, "fp8": 1}[w.weight_dtype]
+    T, H, E, k, I = w.T, w.H, w.E, w.k, w.I_loc
+    A = T * k
+    sh = T if w.shared_expert else 0
+    sh_e = 1 if w.shared_expert else 0
+    work = {
+        "gate_gemm": (2.0 * T * H * E, T * H * ab + E * H * ab),
+        "select": (0.0, T * (4 * E + 8 * k)),
+        "dispatch_gather": (0.0, tokens_local * H * ab + a_loc * H * ab + A * 4),
+        "dispatch_hist": (0.0, A * 4),
+        "dispatch_scatter": (0.0, A * 4 + A * 4 + a_loc * 4),
+        "ffn_gemm1": (4.0 * (a_loc + sh) * H * I, (e_touched + sh_e) * 2 * I * H * wb + (a_loc + sh) * H * ab),
+        "ffn_gemm2": (2.0 * (a_loc + sh) * H * I, (e_touched + sh_e) * I * H * wb + (a_loc + sh) * H * ab),
+        "combine": (0.0, (a_loc + sh) * H * ab + A * 8 + T * H * 4),
+    }
+    return work
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2p", choices=list(DESCR))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one GPU's share on one GPU; --gpus %d is not supported "
+              "(no collectives, no sharding across GPUs)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from workloads import gen
+    import paper_2601_08800_amd as moe
+    from paper_2601_08800_amd.layer import config_from_workload, to_device
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 2
+    moe.load_library()                      # fails loudly when the HIP library is not built
+    w = gen.CONFIGS[args.workload]
+    t0 = time.time()
+    x_np, gate = gen.make_x(w), gen.make_gate(w)
+    experts = gen.make_local_experts(w)
+    shared = gen.make_shared_expert(w) if w.shared_expert else None
+    forced_np = gen.make_forced_routing(w) if w.zipf_s is not None else None
+    print("inputs generated in %.1f s" % (time.time() - t0), file=sys.stderr, flush=True)
+
+    L = moe.MoELayerShare(config_from_workload(w), w.T, gate, experts, shared)
+    x = to_device(x_np)
+    forced = None if forced_np is None else (to_device(forced_np[0]), to_device(forced_np[1]))
+
+    for _ in range(args.warmup):
+        L.forward(x, forced)
+    torch.cuda.synchronize()
+    moe.moe_profile_enable(64 * max(args.steps, 1))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        L.forward(x, forced)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = moe.moe_profile_read()
+    moe.moe_profile_enable(0)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = w.T / (ms_per_step * 1e-3)
+
+    counts = L.counts.cpu().numpy()
+    inv = L.inv.cpu().numpy().reshape(w.T, w.k)
+    a_loc = int(counts.sum())
+    e_touched = int((counts > 0).sum())
+    tokens_local = int((inv >= 0).any(axis=1).sum())
+    n_rescored = int(L.ws[:4].view(torch.int32).item()) if forced is None else 0
+    work = algorithmic_work(w, a_loc, e_touched, tokens_local)
+
+    stages = {}
+    for name, (ms, n) in prof.items():
+        us = ms * 1e3 / args.steps
+        st = {"us_per_step": round(us, 2), "launches_per_step": n / args.steps}
+        if name in work and us > 0:
+            fl, by = work[name]
+            st["GBps"] = round(by / (us * 1e-6) / 1e9, 1)
+            if fl:
+                st["TFLOPs"] = round(fl / (us * 1e-6) / 1e12, 1)
+        stages[name] = st
+
+    dom = max((n for n in prof if n in work), key=lambda n: prof[n][0])
+    fl, by = work[dom]
+    dur = prof[dom][0] * 1e-3 / args.steps
+    peak_tf = PEAK_MFMA_TFLOPS[w.weight_dtype]
+    t_mfma = fl / (peak_tf * 1e12)
+    t_hbm = by / (PEAK_HBM_GBS * 1e9)
+    if t_mfma >= t_hbm:
+        roof = {"bound": "mfma", "achieved": round(fl / dur / 1e12, 2), "peak": peak_tf,
+                "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": round(by / dur / 1e9, 1), "peak": PEAK_HBM_GBS,
+                "unit": "GB/s"}
+    roof["frac"] = round(roof["achieved"] / roof["peak"], 4)
+    roof["traffic"] = None
+    roof["kernel"] = dom
+    roof["kernel_us"] = round(dur * 1e6, 2)
+    roof["algorithmic_flops"] = fl
+    roof["algorithmic_bytes"] = by
+    roof["other_bound_frac"] = round((t_hbm if t_mfma >= t_hbm else t_mfma) / dur, 4)
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            roof["traffic"] = json.load(open(tpath)).get(args.workload, {}).get(dom)
+        except Exception:
+            pass
+
+    out = {
+        "metric": "moe_layer_share_tokens_per_s", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "bf16"}[w.weight_dtype],
+        "data": "synthetic",
+        "config": {"workload": "%s: %s" % (w.name, DESCR[w.name]), "tokens": w.T, "hidden": w.H,
+                   "experts": w.E, "top_k": w.k, "local_experts": w.E_loc,
+                   "inter_local": w.I_loc, "local_assignments": a_loc,
+                   "tokens_rescored_fp64": n_rescored,
+                   "weight_dtype": w.weight_dtype},
+        "roofline": roof,
+        "stages": stages,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, x_np, gate, experts, shared, forced_np,
+                                           args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(w, x_np, gate, experts, shared, forced_np, budget_s):
+    """The oracle as it stands, timed on the host cores on the first n tokens of
+    the same batch (route + dispatch + expert MLP + combine); n grows until the
+    run takes about `budget_s` seconds."""
+    import numpy as np
+    import oracle
+
+    dec = lambda d: None if d is None else {
+        k: (oracle.decode(v) if (v is not None and k.startswith("w_")) else v) for k, v in d.items()}
+    ex, sh = dec(experts), dec(shared)
+    gw = oracle.decode(gate["gate_w"])
+    xf = oracle.decode(x_np)
+
+    def run(n):
+        t0 = time.perf_counter()
+        if forced_np is None:
+            ids, wts, _ = oracle.route(xf[:n], gw, w.k, w.score_fn, w.renormalize, w.routed_scale,
+                                       w.n_groups, w.topk_groups, w.group_score_n,
+                                       gate["logit_bias"], gate["select_bias"])
+        else:
+            ids, wts = forced_np[0][:n], forced_np[1][:n]
+        oracle.layer_share(xf[:n], ids, wts, w.expert_lo, w.e_hi, ex, sh)
+        return time.perf_counter() - t0
+
+    n = min(w.T, 8)
+    dt = run(n)
+    while dt < budget_s / 4 and n < w.T:
+        n = min(w.T, max(n + 1, int(n * min(8.0, budget_s / max(dt, 1e-3)) * 0.8)))
+        dt = run(n)
+    return {"value": round(n / dt, 2), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": "first %d of %d tokens of the same batch, %.1f s" % (n, w.T, dt)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

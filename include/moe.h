@@ -159,6 +159,42 @@ moe_status moe_expert_ffn(const moe_config* cfg, int32_t n_experts_here, const v
 moe_status moe_combine(const moe_config* cfg, int32_t T, const void* ys, const int32_t* inv,
                        const float* topk_w, const void* shared_ys, float* out, void* stream);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the layer; Sec. III-A calls for
+ * profiling data as the analyzer's observations, and the roofline figures need
+ * each kernel's duration on the stream it runs on).  When enabled, every
+ * kernel launch of the four entry points is bracketed by a hipEvent pair taken
+ * from a pool created by moe_profile_enable(); launches beyond the pool are
+ * not recorded.  Events are host objects; no device memory is involved.
+ */
+typedef enum {
+  MOE_K_GATE_NORMS = 0,   /* gate-row norms + counter clear                 */
+  MOE_K_GATE_GEMM = 1,    /* gate logits                                    */
+  MOE_K_SELECT = 2,       /* wavefront top-k                                */
+  MOE_K_RESCORE = 3,      /* fp64 re-scoring of doubtful tokens             */
+  MOE_K_DISPATCH_HIST = 4,
+  MOE_K_DISPATCH_SCAN = 5,
+  MOE_K_DISPATCH_SCATTER = 6,
+  MOE_K_DISPATCH_GATHER = 7,
+  MOE_K_FFN_TILES = 8,
+  MOE_K_FFN_GEMM1 = 9,    /* gate|up projection + SwiGLU                    */
+  MOE_K_FFN_GEMM2 = 10,   /* down projection                                */
+  MOE_K_COMBINE = 11,
+  MOE_K_COUNT = 12
+} moe_kernel_id;
+
+/* max_records > 0: (re)create a pool of that many event pairs and start
+ * recording; 0: stop recording and destroy the pool.  Not thread-safe. */
+moe_status moe_profile_enable(int32_t max_records);
+
+/* Synchronises on the recorded events, then adds up, per moe_kernel_id, the
+ * elapsed milliseconds and the number of recorded launches (host arrays of
+ * MOE_K_COUNT entries), and clears the records (recording stays enabled). */
+moe_status moe_profile_read(double* total_ms, int32_t* launches);
+
+/* Static name of a kernel id (host pointer). */
+const char* moe_kernel_name(int32_t id);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,7 +14,9 @@ _LIB_PATH = os.path.join(_PKG, "libmoe.so")
 _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatch",
-           "moe_expert_ffn", "moe_combine")
+           "moe_expert_ffn", "moe_combine", "moe_profile_enable", "moe_profile_read",
+           "moe_kernel_name")
+MOE_K_COUNT = 12
 
 
 class MoEConfig(ctypes.Structure):
@@ -65,6 +67,12 @@ def load_library():
         lib.moe_expert_ffn.argtypes = [cfgp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_combine.restype = ctypes.c_int
         lib.moe_combine.argtypes = [cfgp, i32, vp, vp, vp, vp, vp, vp]
+        lib.moe_profile_enable.restype = ctypes.c_int
+        lib.moe_profile_enable.argtypes = [i32]
+        lib.moe_profile_read.restype = ctypes.c_int
+        lib.moe_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+        lib.moe_kernel_name.restype = ctypes.c_char_p
+        lib.moe_kernel_name.argtypes = [i32]
         _lib = lib
     return _lib
 
@@ -136,3 +144,16 @@ def moe_combine(cfg, T, ys, inv, topk_w, shared_ys, out, stream=None):
     st = load_library().moe_combine(ctypes.byref(cfg), T, _ptr(ys), _ptr(inv), _ptr(topk_w),
                                     _ptr(shared_ys), _ptr(out), _stream(stream))
     _check(st, "moe_combine")
+
+
+def moe_profile_enable(max_records: int):
+    _check(load_library().moe_profile_enable(max_records), "moe_profile_enable")
+
+
+def moe_profile_read():
+    """{kernel name: (total ms, launches)} of the launches recorded since the last read."""
+    lib = load_library()
+    ms = (ctypes.c_double * MOE_K_COUNT)()
+    n = (ctypes.c_int32 * MOE_K_COUNT)()
+    _check(lib.moe_profile_read(ms, n), "moe_profile_read")
+    return {lib.moe_kernel_name(i).decode(): (ms[i], n[i]) for i in range(MOE_K_COUNT) if n[i]}

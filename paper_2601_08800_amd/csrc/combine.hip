@@ -103,11 +103,11 @@ hipError_t launch_combine(const moe_config& c, int T, const void* ys, const int3
                           const float* w, const void* shared_ys, float* out, hipStream_t s) {
   const dim3 grid((T + 3) / 4), block(256);
   if (c.act_dtype == MOE_BF16) {
-    hipLaunchKernelGGL(combine_bf16_kernel, grid, block, 0, s, static_cast<const uint4*>(ys), inv,
+    MOE_LAUNCH(MOE_K_COMBINE, combine_bf16_kernel, grid, block, 0, s, static_cast<const uint4*>(ys), inv,
                        w, static_cast<const uint4*>(shared_ys), reinterpret_cast<float4*>(out), T,
                        c.top_k, c.hidden / 8);
   } else {
-    hipLaunchKernelGGL(combine_f32_kernel, grid, block, 0, s, static_cast<const float4*>(ys), inv,
+    MOE_LAUNCH(MOE_K_COMBINE, combine_f32_kernel, grid, block, 0, s, static_cast<const float4*>(ys), inv,
                        w, static_cast<const float4*>(shared_ys), reinterpret_cast<float4*>(out), T,
                        c.top_k, c.hidden / 4);
   }

@@ -141,14 +141,14 @@ hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int3
   const int k = c.top_k;
   const int A = T * k;
   const int E_loc = c.expert_hi - c.expert_lo;
-  hipLaunchKernelGGL(dispatch_index_kernel<0>, dim3(ws.n_blocks), dim3(64), 0, s, ids, A,
+  MOE_LAUNCH(MOE_K_DISPATCH_HIST, dispatch_index_kernel<0>, dim3(ws.n_blocks), dim3(64), 0, s, ids, A,
                      c.expert_lo, E_loc, ws.block_hist, perm, inv);
-  hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(256), 0, s, ws.block_hist, ws.n_blocks,
+  MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_scan_kernel, dim3(1), dim3(256), 0, s, ws.block_hist, ws.n_blocks,
                      E_loc, counts, offsets);
-  hipLaunchKernelGGL(dispatch_index_kernel<1>, dim3(ws.n_blocks), dim3(64), 0, s, ids, A,
+  MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_index_kernel<1>, dim3(ws.n_blocks), dim3(64), 0, s, ids, A,
                      c.expert_lo, E_loc, ws.block_hist, perm, inv);
   const int row16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
-  hipLaunchKernelGGL(dispatch_gather_kernel<8>, dim3((T + 3) / 4), dim3(256), 0, s,
+  MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_gather_kernel<8>, dim3((T + 3) / 4), dim3(256), 0, s,
                      static_cast<const uint4*>(x), inv, static_cast<uint4*>(xs), T, k, row16);
   return hipGetLastError();
 }

@@ -329,7 +329,7 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
                       const FfnWs& ws, hipStream_t s) {
   const int H = c.hidden, I = c.inter_local;
   const int max_mt = rows_capacity / BM + n_experts;
-  hipLaunchKernelGGL(ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
+  MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
                      rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles);
   const int nt1 = (I + BN1 - 1) / BN1, nt2 = (H + BN2 - 1) / BN2;
   auto k1 = ffn_gemm_kernel<BM, BN1, WM, WN1, true, FP8>;
@@ -343,10 +343,10 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
                         hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
     configured = true;
   }
-  hipLaunchKernelGGL(k1, dim3(size_t(max_mt) * nt1), dim3(256), lds1, s,
+  MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(size_t(max_mt) * nt1), dim3(256), lds1, s,
                      static_cast<const uint16_t*>(xs), w_gate, w_up, s_gate, s_up,
                      static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
-  hipLaunchKernelGGL(k2, dim3(size_t(max_mt) * nt2), dim3(256), lds2, s,
+  MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(size_t(max_mt) * nt2), dim3(256), lds2, s,
                      static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr, s_down,
                      (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
 }
@@ -362,13 +362,13 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
   if (c.act_dtype == MOE_F32) {
     const int BM = 64;
     const int max_mt = rows_capacity / BM + n_experts;
-    hipLaunchKernelGGL(ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
+    MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
                        rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles);
-    hipLaunchKernelGGL(ffn_f32_kernel<true>, dim3(size_t(max_mt) * ((I + 63) / 64)), dim3(256), 0,
+    MOE_LAUNCH(MOE_K_FFN_GEMM1, ffn_f32_kernel<true>, dim3(size_t(max_mt) * ((I + 63) / 64)), dim3(256), 0,
                        s, static_cast<const float*>(xs), static_cast<const float*>(w_gate),
                        static_cast<const float*>(w_up), static_cast<float*>(ws.hmid), I, H,
                        ws.tiles);
-    hipLaunchKernelGGL(ffn_f32_kernel<false>, dim3(size_t(max_mt) * ((H + 63) / 64)), dim3(256), 0,
+    MOE_LAUNCH(MOE_K_FFN_GEMM2, ffn_f32_kernel<false>, dim3(size_t(max_mt) * ((H + 63) / 64)), dim3(256), 0,
                        s, static_cast<const float*>(ws.hmid), static_cast<const float*>(w_down),
                        nullptr, static_cast<float*>(ys), H, I, ws.tiles);
     return hipGetLastError();

@@ -49,6 +49,17 @@ struct FfnWs {
 };
 FfnWs carve_ffn(void* ws, int rows_capacity, int n_experts, int I_loc, int act_bytes);
 
+// ---- optional per-kernel event timing ---------------------------------------
+void prof_mark(int kernel_id, hipStream_t s, bool begin);
+extern bool g_prof_on;
+// Launch `kernel` and, when profiling is on, bracket it with an event pair.
+#define MOE_LAUNCH(id, kernel, grid, block, lds, stream, ...)            \
+  do {                                                                   \
+    if (::moe::g_prof_on) ::moe::prof_mark(id, stream, true);            \
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);   \
+    if (::moe::g_prof_on) ::moe::prof_mark(id, stream, false);           \
+  } while (0)
+
 // ---- launchers (return hipGetLastError() of their launches) ---------------
 hipError_t launch_route(const moe_config& c, int T, const void* x, const void* gate_w,
                         const float* logit_bias, const float* select_bias,

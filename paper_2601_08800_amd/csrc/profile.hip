@@ -1,0 +1,74 @@
+// Per-kernel event timing used by the benchmark (see moe_profile_* in moe.h).
+#include <vector>
+
+#include "moe_internal.h"
+
+namespace moe {
+
+bool g_prof_on = false;
+
+namespace {
+struct Rec { int id; hipEvent_t a, b; };
+std::vector<Rec> g_pool;
+size_t g_used = 0;
+bool g_open = false;   // a begin mark was taken and awaits its end mark
+}  // namespace
+
+void prof_mark(int kernel_id, hipStream_t s, bool begin) {
+  if (begin) {
+    if (g_used >= g_pool.size()) { g_open = false; return; }
+    g_pool[g_used].id = kernel_id;
+    hipEventRecord(g_pool[g_used].a, s);
+    g_open = true;
+  } else if (g_open) {
+    hipEventRecord(g_pool[g_used].b, s);
+    ++g_used;
+    g_open = false;
+  }
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+moe_status moe_profile_enable(int32_t max_records) {
+  if (max_records < 0) return MOE_ERR_INVALID_ARG;
+  g_prof_on = false;
+  for (auto& r : g_pool) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  g_pool.clear();
+  g_used = 0;
+  g_open = false;
+  if (max_records == 0) return MOE_OK;
+  g_pool.resize(max_records);
+  for (auto& r : g_pool) {
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess)
+      return MOE_ERR_DEVICE;
+  }
+  g_prof_on = true;
+  return MOE_OK;
+}
+
+moe_status moe_profile_read(double* total_ms, int32_t* launches) {
+  if (!total_ms || !launches) return MOE_ERR_INVALID_ARG;
+  for (int i = 0; i < MOE_K_COUNT; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  for (size_t i = 0; i < g_used; ++i) {
+    float ms = 0.f;
+    if (hipEventSynchronize(g_pool[i].b) != hipSuccess) return MOE_ERR_DEVICE;
+    if (hipEventElapsedTime(&ms, g_pool[i].a, g_pool[i].b) != hipSuccess) return MOE_ERR_DEVICE;
+    total_ms[g_pool[i].id] += ms;
+    launches[g_pool[i].id] += 1;
+  }
+  g_used = 0;
+  return MOE_OK;
+}
+
+const char* moe_kernel_name(int32_t id) {
+  static const char* names[MOE_K_COUNT] = {
+      "gate_norms", "gate_gemm", "select", "rescore", "dispatch_hist", "dispatch_scan",
+      "dispatch_scatter", "dispatch_gather", "ffn_tiles", "ffn_gemm1", "ffn_gemm2", "combine"};
+  return (id >= 0 && id < MOE_K_COUNT) ? names[id] : "unknown";
+}
+
+}  // extern "C"

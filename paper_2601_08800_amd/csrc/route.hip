@@ -569,16 +569,16 @@ void launch_select_and_recheck(const SelCfg& sc, const moe_config& c, int T, con
                                const float* select_bias, const float* logits_in,
                                const float* logits, int32_t* ids, float* w, const RouteWs& ws,
                                hipStream_t s) {
-  hipLaunchKernelGGL(route_select_kernel<EPL>, dim3((T + 3) / 4), dim3(256), 0, s, sc, T, logits,
+  MOE_LAUNCH(MOE_K_SELECT, route_select_kernel<EPL>, dim3((T + 3) / 4), dim3(256), 0, s, sc, T, logits,
                      logit_bias, select_bias, ws.xnorm2, ws.wnorm2, ids, w, ws.counters,
                      ws.recheck);
   const int grid = T < 4096 ? T : 4096;
   if (c.act_dtype == MOE_BF16)
-    hipLaunchKernelGGL((route_recheck_kernel<EPL, true>), dim3(grid), dim3(256), 0, s, sc,
+    MOE_LAUNCH(MOE_K_RESCORE, (route_recheck_kernel<EPL, true>), dim3(grid), dim3(256), 0, s, sc,
                        c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
                        ws.wnorm2, ids, w, ws.counters, ws.recheck);
   else
-    hipLaunchKernelGGL((route_recheck_kernel<EPL, false>), dim3(grid), dim3(256), 0, s, sc,
+    MOE_LAUNCH(MOE_K_RESCORE, (route_recheck_kernel<EPL, false>), dim3(grid), dim3(256), 0, s, sc,
                        c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
                        ws.wnorm2, ids, w, ws.counters, ws.recheck);
 }
@@ -598,23 +598,23 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   sc.chain_err = 0.f; sc.have_norms = 0;
   const void* gw_for_norm = logits_in ? nullptr : gate_w;
   if (bf16)
-    hipLaunchKernelGGL(gate_wnorm_kernel<true>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm, E,
+    MOE_LAUNCH(MOE_K_GATE_NORMS, gate_wnorm_kernel<true>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm, E,
                        H, ws.wnorm2, ws.counters);
   else
-    hipLaunchKernelGGL(gate_wnorm_kernel<false>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm,
+    MOE_LAUNCH(MOE_K_GATE_NORMS, gate_wnorm_kernel<false>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm,
                        E, H, ws.wnorm2, ws.counters);
   if (!logits_in) {
     logits = ws.logits;
     sc.have_norms = 1;
     if (bf16) {
       const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN);
-      hipLaunchKernelGGL(gate_mfma_kernel<kGateChainSteps>, grid, dim3(256), 0, s,
+      MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(256), 0, s,
                          static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T,
                          H, E, ws.logits, ws.xnorm2);
       // chains of kGateChainSteps*64 products; +2 for the flush and the store
       sc.chain_err = (2.f * kGateChainSteps * GBK + 2.f) * kUlp;
     } else {
-      hipLaunchKernelGGL(gate_f64_kernel, dim3(T), dim3(256), 0, s, static_cast<const float*>(x),
+      MOE_LAUNCH(MOE_K_GATE_GEMM, gate_f64_kernel, dim3(T), dim3(256), 0, s, static_cast<const float*>(x),
                          static_cast<const float*>(gate_w), T, H, E, ws.logits, ws.xnorm2);
       // fp64 sums: the only error is the fp32 store, covered by the 2 ulp term
       sc.chain_err = 1e-12f;
