@@ -40,32 +40,42 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 
 // ------------------------------------------------------------- tile table
 // tiles[0] = number of M tiles; then (expert, first row, end row) per tile.
+// `balance`: an expert's rows are cut into ceil(M/bm) tiles of equal height
+// (rounded up to 32 rows) instead of full tiles plus a short tail.
 __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restrict__ offsets,
                                                        int n_experts, int bm, int rows_capacity,
-                                                       int32_t* __restrict__ tiles, int max_tiles) {
+                                                       int32_t* __restrict__ tiles, int max_tiles,
+                                                       int balance) {
   __shared__ int32_t start[513];
+  __shared__ int32_t off[513];
+  for (int e = threadIdx.x; e <= n_experts; e += blockDim.x) {
+    int o = offsets[e];
+    o = o < 0 ? 0 : o;
+    off[e] = o > rows_capacity ? rows_capacity : o;
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
     int run = 0;
     for (int e = 0; e < n_experts; ++e) {
-      int lo = offsets[e], hi = offsets[e + 1];
-      lo = lo < 0 ? 0 : lo;
-      hi = hi > rows_capacity ? rows_capacity : hi;
+      const int lo = off[e], hi = off[e + 1];
       start[e] = run;
       run += hi > lo ? (hi - lo + bm - 1) / bm : 0;
     }
-    start[n_experts] = run;
     tiles[0] = run < max_tiles ? run : max_tiles;
   }
   __syncthreads();
   for (int e = threadIdx.x; e < n_experts; e += blockDim.x) {
-    int lo = offsets[e], hi = offsets[e + 1];
-    lo = lo < 0 ? 0 : lo;
-    hi = hi > rows_capacity ? rows_capacity : hi;
+    const int lo = off[e], hi = off[e + 1];
     int t = start[e];
-    for (int r = lo; r < hi && t < max_tiles; r += bm, ++t) {
+    int step = bm;
+    if (balance && hi > lo) {
+      const int nt = (hi - lo + bm - 1) / bm;
+      step = (((hi - lo + nt - 1) / nt) + 31) / 32 * 32;
+    }
+    for (int r = lo; r < hi && t < max_tiles; r += step, ++t) {
       tiles[1 + 3 * t] = e;
       tiles[2 + 3 * t] = r;
-      tiles[3 + 3 * t] = (r + bm < hi) ? r + bm : hi;
+      tiles[3 + 3 * t] = (r + step < hi) ? r + step : hi;
     }
   }
 }
@@ -257,6 +267,178 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
     }
 }
 
+// ------------------------------------------------- MFMA GEMM, 256-row tiles
+// Prefill-sized groups: block tile 256 rows x 256 weight rows (DUAL: 128 gate
+// + the matching 128 up rows), K step 64, four wavefronts side by side along N
+// so that each one spans all 256 rows: a short tile (ragged group tail) then
+// idles no wavefront, it just skips the 32-row MFMA blocks past its last row.
+// Operands go global -> LDS directly (16 B per lane, no register staging); the
+// per-lane global address is permuted so that the linear LDS write of a
+// wavefront lands in the XOR-swizzled layout the MFMA operand reads expect.
+// Workgroup ids are remapped so that each XCD (own L2) walks a contiguous run
+// of tiles: neighbours in that run share the activation panel (same M tile)
+// and, one group of N tiles later, the expert's weight panels.
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// NB = number of 32-row blocks of the tile that hold valid rows (1..8); a
+// compile-time constant so that the K loop is free of branches.
+template <bool DUAL, int NB>
+__device__ __forceinline__ void gemm256_body(const uint16_t* __restrict__ A,
+                                             const uint16_t* __restrict__ Be0,
+                                             const uint16_t* __restrict__ Be1,
+                                             uint16_t* __restrict__ C, int N, int K, int row0,
+                                             int row1, int n0, uint4* smem) {
+  constexpr int SLOTS = 256 * 8;         // 16-byte pieces per operand buffer
+  uint4* As = smem;                      // [2][SLOTS]
+  uint4* Bs = smem + 2 * SLOTS;          // [2][SLOTS]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ksteps = K / BK;
+
+  // lane's place inside a group of 8 rows: row l/8, piece (l%8) ^ (l/8)
+  const int lrow = lane >> 3;
+  const int lcol = ((lane & 7) ^ lrow) * 8;
+  const uint16_t* asrc[NB];
+  const uint16_t* bsrc[8];
+#pragma unroll
+  for (int q = 0; q < NB; ++q) {
+    int r = row0 + (q * 4 + wave) * 8 + lrow;
+    r = r < row1 ? r : row1 - 1;
+    asrc[q] = A + size_t(r) * K + lcol;
+  }
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const int rg = q * 4 + wave;
+    const int br = rg * 8 + lrow;        // LDS row of the weight tile
+    const uint16_t* base = (DUAL && q >= 4) ? Be1 : Be0;
+    int n = n0 + ((DUAL && q >= 4) ? br - 128 : br);
+    n = n < N ? n : N - 1;
+    bsrc[q] = base + size_t(n) * K + lcol;
+  }
+  auto issue = [&](int ks, int buf) {
+    const int kcol = ks * BK;
+#pragma unroll
+    for (int q = 0; q < NB; ++q)
+      __builtin_amdgcn_global_load_lds((gptr_t)(asrc[q] + kcol),
+                                       (lptr_t)(As + buf * SLOTS + (q * 4 + wave) * 64), 16, 0, 0);
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[q] + kcol),
+                                       (lptr_t)(Bs + buf * SLOTS + (q * 4 + wave) * 64), 16, 0, 0);
+  };
+
+  f32x16 acc[NB][2];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+  // LDS rows of this wavefront's two 32-column blocks of the weight tile
+  const int brow0 = DUAL ? wave * 32 : wave * 64;
+  const int brow1 = DUAL ? 128 + wave * 32 : wave * 64 + 32;
+
+  issue(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0f70);    // vmcnt(0)
+  __syncthreads();
+  for (int ks = 0; ks < ksteps; ++ks) {
+    const int buf = ks & 1;
+    if (ks + 1 < ksteps) issue(ks + 1, buf ^ 1);
+    const uint4* Ab = As + buf * SLOTS;
+    const uint4* Bb = Bs + buf * SLOTS;
+    // operand fragments are read one K sub-step ahead of the MFMAs that use them
+    uint4 fa[2][NB], fb[2][2];
+    auto read_frags = [&](int kk, int set) {
+      const int piece = kk * 2 + (lane >> 5);
+      fb[set][0] = Bb[swz(brow0 + (lane & 31), piece)];
+      fb[set][1] = Bb[swz(brow1 + (lane & 31), piece)];
+#pragma unroll
+      for (int i = 0; i < NB; ++i) fa[set][i] = Ab[swz(i * 32 + (lane & 31), piece)];
+    };
+    read_frags(0, 0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int set = kk & 1;
+      // nothing may move across this point: the reads below belong to the
+      // next sub-step and must stay ahead of this sub-step's MFMAs
+      __builtin_amdgcn_sched_barrier(0);
+      if (kk < 3) read_frags(kk + 1, set ^ 1);
+      const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[set][0]);
+      const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[set][1]);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, fa[set][i]);
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
+      }
+      if (kk < 3 && NB >= 2) {
+        // one LDS read slipped in after each of the first MFMAs
+#pragma unroll
+        for (int i = 0; i < NB + 2; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB - (NB + 2), 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // the next step's tiles have landed
+    __syncthreads();
+  }
+
+  // D layout: lane l, register q -> row (q/4)*8 + (l/32)*4 + q%4, col l%32
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int row = row0 + i * 32 + (q >> 2) * 8 + (lane >> 5) * 4 + (q & 3);
+      if (row >= row1) continue;
+      if (DUAL) {
+        const int col = n0 + wave * 32 + (lane & 31);
+        if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(silu_mul(acc[i][0][q], acc[i][1][q]));
+      } else {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int col = n0 + wave * 64 + j * 32 + (lane & 31);
+          if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(acc[i][j][q]);
+        }
+      }
+    }
+  }
+}
+
+template <bool DUAL>
+__global__ __launch_bounds__(256) void ffn_gemm256_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
+    const uint16_t* __restrict__ B1, uint16_t* __restrict__ C, int N, int K,
+    const int32_t* __restrict__ tiles) {
+  constexpr int BN = DUAL ? 128 : 256;   // output columns per block
+  extern __shared__ uint4 smem[];
+  const int n_ntiles = (N + BN - 1) / BN;
+  const int total = tiles[0] * n_ntiles;
+  const int per_xcd = (total + 7) >> 3;
+  const int pid = blockIdx.x;
+  const int logical = (pid & 7) * per_xcd + (pid >> 3);
+  if ((pid >> 3) >= per_xcd || logical >= total) return;
+  const int mtile = logical / n_ntiles, ntile = logical - mtile * n_ntiles;
+  const int e = tiles[1 + 3 * mtile], row0 = tiles[2 + 3 * mtile], row1 = tiles[3 + 3 * mtile];
+  const int n0 = ntile * BN;
+  const uint16_t* Be0 = B0 + size_t(e) * N * K;
+  const uint16_t* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
+  switch ((row1 - row0 + 31) >> 5) {     // valid 32-row blocks of this tile
+    case 1: gemm256_body<DUAL, 1>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
+    case 2: gemm256_body<DUAL, 2>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
+    case 3: gemm256_body<DUAL, 3>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
+    case 4: gemm256_body<DUAL, 4>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
+    case 5: gemm256_body<DUAL, 5>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
+    case 6: gemm256_body<DUAL, 6>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
+    case 7: gemm256_body<DUAL, 7>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
+    default: gemm256_body<DUAL, 8>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
+  }
+}
+
 // ------------------------------------------------------------ fp32 GEMM
 // Plain VALU kernel for the fp32 configuration: 64x64 tile, 16x16 threads,
 // 4x4 outputs per thread, K step 16.
@@ -330,7 +512,7 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
   const int H = c.hidden, I = c.inter_local;
   const int max_mt = rows_capacity / BM + n_experts;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
-                     rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles);
+                     rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0);
   const int nt1 = (I + BN1 - 1) / BN1, nt2 = (H + BN2 - 1) / BN2;
   auto k1 = ffn_gemm_kernel<BM, BN1, WM, WN1, true, FP8>;
   auto k2 = ffn_gemm_kernel<BM, BN2, WM, WN2, false, FP8>;
@@ -351,6 +533,34 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
                      (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
 }
 
+void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const int32_t* offsets,
+                    int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
+                    void* ys, const FfnWs& ws, hipStream_t s) {
+  const int H = c.hidden, I = c.inter_local;
+  const int max_mt = rows_capacity / 256 + n_experts;
+  MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, 256,
+             rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 1);
+  const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
+  auto k1 = ffn_gemm256_kernel<true>;
+  auto k2 = ffn_gemm256_kernel<false>;
+  constexpr int lds = 4 * 256 * 8 * 16;   // A and B, double buffered: 128 KB
+  static bool configured = false;
+  if (!configured) {
+    hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    hipFuncSetAttribute(reinterpret_cast<const void*>(k2),
+                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    configured = true;
+  }
+  const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt * nt2 + 7) / 8 * 8;
+  MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(256), lds, s, static_cast<const uint16_t*>(xs),
+             static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
+             static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
+  MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(g2), dim3(256), lds, s,
+             static_cast<const uint16_t*>(ws.hmid), static_cast<const uint16_t*>(w_down),
+             (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
+}
+
 }  // namespace
 
 hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
@@ -363,7 +573,7 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
     const int BM = 64;
     const int max_mt = rows_capacity / BM + n_experts;
     MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
-                       rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles);
+                       rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0);
     MOE_LAUNCH(MOE_K_FFN_GEMM1, ffn_f32_kernel<true>, dim3(size_t(max_mt) * ((I + 63) / 64)), dim3(256), 0,
                        s, static_cast<const float*>(xs), static_cast<const float*>(w_gate),
                        static_cast<const float*>(w_up), static_cast<float*>(ws.hmid), I, H,
@@ -384,6 +594,8 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
   } else if (avg <= 64) {
     if (fp8) launch_mfma_pair<64, 128, 64, 32, 256, 64, true>(MOE_FFN_ARGS);
     else launch_mfma_pair<64, 128, 64, 32, 256, 64, false>(MOE_FFN_ARGS);
+  } else if (!fp8 && H % BK == 0 && I % BK == 0) {
+    launch_mfma256(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
   } else {
     if (fp8) launch_mfma_pair<128, 64, 64, 32, 128, 64, true>(MOE_FFN_ARGS);
     else launch_mfma_pair<128, 64, 64, 32, 128, 64, false>(MOE_FFN_ARGS);

@@ -57,7 +57,7 @@ DispatchWs carve_dispatch(void* ws, int T, int k, int E_loc) {
   size_t A = size_t(T) * k;
   d.n_blocks = int((A + kDispatchChunk - 1) / kDispatchChunk);
   d.block_hist = static_cast<int32_t*>(ws);
-  d.bytes = align_up(size_t(d.n_blocks) * E_loc * 4);
+  d.bytes = align_up(size_t(d.n_blocks) * (kDispatchChunk / 256) * E_loc * 4);
   return d;
 }
 

@@ -32,8 +32,8 @@ RouteWs carve_route(void* ws, int T, int E);
 // dispatch
 constexpr int kDispatchChunk = 1024;          // assignments per histogram block
 struct DispatchWs {
-  int32_t* block_hist; // [n_blocks, E_loc] -> after the scan: start position of
-                       // the block's first assignment of each expert
+  int32_t* block_hist; // [n_blocks * 4 sub-chunks, E_loc] -> after the scan: start
+                       // position of the sub-chunk's first assignment of each expert
   int n_blocks;
   size_t bytes;
 };
