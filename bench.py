@@ -110,7 +110,11 @@ def main():
     a_loc = int(counts.sum())
     e_touched = int((counts > 0).sum())
     tokens_local = int((inv >= 0).any(axis=1).sum())
-    n_rescored = int(L.ws[:4].view(torch.int32).item()) if forced is None else 0
+    n_rescored = 0
+    if forced is None:          # the counter lives in the workspace: read it right after a route call
+        L.route(x)
+        torch.cuda.synchronize()
+        n_rescored = int(L.ws[:4].view(torch.int32).item())
     work = algorithmic_work(w, a_loc, e_touched, tokens_local)
 
     stages = {}

@@ -82,6 +82,7 @@ __device__ __forceinline__ double wave_dot64(const void* xrow, const void* wrow,
   if (BF16) {
     const uint4* xa = static_cast<const uint4*>(xrow);
     const uint4* wa = static_cast<const uint4*>(wrow);
+#pragma unroll 4
     for (int c = lane; c < H / 8; c += 64) {
       const uint4 a = xa[c], b = wa[c];
       const uint32_t av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
@@ -94,6 +95,7 @@ __device__ __forceinline__ double wave_dot64(const void* xrow, const void* wrow,
   } else {
     const float4* xa = static_cast<const float4*>(xrow);
     const float4* wa = static_cast<const float4*>(wrow);
+#pragma unroll 4
     for (int c = lane; c < H / 4; c += 64) {
       const float4 a = xa[c], b = wa[c];
       acc = fma((double)a.x, (double)b.x, acc);
@@ -274,14 +276,19 @@ struct Keys {
   FT sc[EPL];    // value the weight is made of: logit (softmax) or sigmoid score
 };
 
-template <typename FT, int EPL>
+template <typename FT>
+struct Groups {
+  uint64_t kept;    // bit g: group g survives the group limit
+  bool certain;     // the cut between kept and dropped groups holds for any keys within eps
+  uint32_t need;    // bit per slot: the expert may be one of its group's group_score_n largest
+};
+
+template <typename FT>
 struct Picks {
   int id;        // lane j < k: j-th pick
   FT sc;         // its logit / score
   FT low;        // smallest lower bound of a picked key
   bool certain;  // every comparison held with the error intervals apart
-  bool groups_certain;
-  uint32_t elig; // bit per slot: expert may be selected (valid and in a kept group)
 };
 
 // Fast keys of token t from the stage-1 logits.
@@ -319,23 +326,47 @@ __device__ __forceinline__ void fast_keys(const SelCfg& c, const float* __restri
   }
 }
 
-// Group limit and top-k over one wavefront.  Ties go to the lowest index.
+// Group limit: keep the Kg groups with the largest sum of their gn largest
+// keys; ties go to the lowest group.  Lane g ends up holding group g's score.
 template <typename FT, int EPL>
-__device__ __forceinline__ void select_topk(const SelCfg& c, const Keys<FT, EPL>& K, int lane,
-                                            Picks<FT, EPL>& P) {
-  uint32_t elig = 0;
+__device__ __forceinline__ void group_stage(const SelCfg& c, const Keys<FT, EPL>& K, int lane,
+                                            Groups<FT>& Gp) {
+  const int gs = c.E / c.G;
+  FT gsum = 0, gerr = 0;          // lane g: score of group g and the bound on its error
+  uint32_t need = 0;
+  if (64 % gs == 0 && c.gn <= 2 && c.E % 64 == 0) {
+    // groups are aligned runs of gs lanes inside a slot: butterfly (max1, max2,
+    // max eps, min lower bound of the two largest) over each run, all groups at once
+    const int per_slot = 64 / gs;
 #pragma unroll
-  for (int i = 0; i < EPL; ++i)
-    if (i * 64 + lane < c.E) elig |= 1u << i;
-  P.certain = true;
-  P.groups_certain = true;
-
-  if (c.G > 1) {
-    const int gs = c.E / c.G;
-    FT gsum = 0, gerr = 0;        // lane g holds group g
+    for (int i = 0; i < EPL; ++i) {
+      if (i * 64 >= c.E) break;
+      FT m1 = K.key[i], m2 = -INFINITY, me = K.eps[i];
+      FT l1 = K.key[i] - K.eps[i], l2 = -INFINITY;      // two largest lower bounds
+      for (int off = 1; off < gs; off <<= 1) {
+        const FT o1 = __shfl_xor(m1, off), o2 = __shfl_xor(m2, off), oe = __shfl_xor(me, off);
+        const FT p1 = __shfl_xor(l1, off), p2 = __shfl_xor(l2, off);
+        const FT lo = m1 < o1 ? m1 : o1, hi2 = m2 > o2 ? m2 : o2;
+        m1 = m1 > o1 ? m1 : o1;
+        m2 = lo > hi2 ? lo : hi2;
+        me = me > oe ? me : oe;
+        const FT ql = l1 < p1 ? l1 : p1, qh = l2 > p2 ? l2 : p2;
+        l1 = l1 > p1 ? l1 : p1;
+        l2 = ql > qh ? ql : qh;
+      }
+      const FT sum = c.gn == 2 ? m1 + m2 : m1;
+      const FT nth_low = c.gn == 2 ? l2 : l1;            // <= the gn-th largest exact key
+      if (K.key[i] + K.eps[i] >= nth_low) need |= 1u << i;
+      // lane g fetches its group's values from the first lane of the run
+      const int g0 = i * per_slot;
+      const int src = (lane >= g0 && lane < g0 + per_slot) ? (lane - g0) * gs : 0;
+      const FT s_ = __shfl(sum, src), e_ = __shfl(me, src);
+      if (lane >= g0 && lane < g0 + per_slot) { gsum = s_; gerr = e_ * (FT)c.gn; }
+    }
+  } else {
     for (int g = 0; g < c.G; ++g) {
       uint32_t taken = 0;
-      FT sum = 0, me = 0;
+      FT sum = 0, me = 0, nth_low = INFINITY;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
         const int e = i * 64 + lane;
@@ -353,33 +384,54 @@ __device__ __forceinline__ void select_topk(const SelCfg& c, const Keys<FT, EPL>
         }
         wave_argmax(v, idx);
         sum += v;
+        nth_low = v - me;       // keys come in descending order; me bounds every eps
         if ((idx & 63) == lane) taken |= 1u << (idx >> 6);
+      }
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        const int e = i * 64 + lane;
+        if (e < c.E && e / gs == g && K.key[i] + K.eps[i] >= nth_low) need |= 1u << i;
       }
       if (lane == g) { gsum = sum; gerr = me * (FT)c.gn; }
     }
-    uint64_t kept = 0;
-    FT low = INFINITY;
-    for (int r = 0; r < c.Kg; ++r) {
-      FT v = gsum; int idx = (lane < c.G && !(kept >> lane & 1)) ? lane : INT_MAX;
-      wave_argmax(v, idx);
-      kept |= uint64_t(1) << idx;
-      const FT lo = __shfl(gsum - gerr, idx);
-      low = lo < low ? lo : low;
-    }
-    FT hi = (lane < c.G && !(kept >> lane & 1)) ? gsum + gerr : -INFINITY;
-    hi = wave_max(hi);
-    if (!(low > hi)) P.groups_certain = false;
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-      const int e = i * 64 + lane;
-      if (e < c.E && !(kept >> (e / gs) & 1)) elig &= ~(1u << i);
-    }
   }
-  P.elig = elig;
+  uint64_t kept = 0;
+  FT low = INFINITY;
+  for (int r = 0; r < c.Kg; ++r) {
+    FT v = gsum; int idx = (lane < c.G && !(kept >> lane & 1)) ? lane : INT_MAX;
+    wave_argmax(v, idx);
+    kept |= uint64_t(1) << idx;
+    const FT lo = __shfl(gsum - gerr, idx);
+    low = lo < low ? lo : low;
+  }
+  FT hi = (lane < c.G && !(kept >> lane & 1)) ? gsum + gerr : -INFINITY;
+  hi = wave_max(hi);
+  Gp.kept = kept;
+  Gp.certain = (c.Kg >= c.G) || (low > hi);
+  Gp.need = need;
+}
 
+// Eligibility bits per slot: valid expert whose group is kept.
+template <int EPL>
+__device__ __forceinline__ uint32_t eligible_mask(const SelCfg& c, uint64_t kept, int lane) {
+  uint32_t elig = 0;
+  const int gs = c.E / c.G;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int e = i * 64 + lane;
+    if (e < c.E && (c.G <= 1 || (kept >> (e / gs) & 1))) elig |= 1u << i;
+  }
+  return elig;
+}
+
+// Top-k among the eligible experts, k successive arg-max reductions; ties go to
+// the lowest expert index.
+template <typename FT, int EPL>
+__device__ __forceinline__ void topk_stage(const SelCfg& c, const Keys<FT, EPL>& K, uint32_t elig,
+                                           int lane, Picks<FT>& P) {
   uint32_t taken = 0;
   FT prev_lo = INFINITY, low = INFINITY;
-  P.id = -1; P.sc = 0;
+  P.id = -1; P.sc = 0; P.certain = true;
   for (int j = 0; j < c.k; ++j) {
     FT v = 0; int idx = INT_MAX;
 #pragma unroll
@@ -414,14 +466,13 @@ __device__ __forceinline__ void select_topk(const SelCfg& c, const Keys<FT, EPL>
   const bool some = __ballot(any) != 0;
   hi = wave_max(any ? hi : (FT)-INFINITY);
   if (some && !(prev_lo > hi)) P.certain = false;
-  if (!P.groups_certain) P.certain = false;
   P.low = low;
 }
 
 // Weights of the picked experts; lane j < k returns w[t,j].
 template <typename FT, int EPL>
 __device__ __forceinline__ FT pick_weight(const SelCfg& c, const Keys<FT, EPL>& K,
-                                          const Picks<FT, EPL>& P, int lane) {
+                                          const Picks<FT>& P, int lane) {
   const bool mine = lane < c.k;
   FT num, den;
   if (c.score_fn == MOE_SCORE_SOFTMAX) {
@@ -461,9 +512,12 @@ __global__ __launch_bounds__(256) void route_select_kernel(
   Keys<float, EPL> K;
   const float xn = c.have_norms ? sqrtf(xnorm2[t]) : 0.f;
   fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
-  Picks<float, EPL> P;
-  select_topk<float, EPL>(c, K, lane, P);
-  if (P.certain) {
+  Groups<float> Gp;
+  Gp.kept = 0; Gp.certain = true; Gp.need = 0;
+  if (c.G > 1) group_stage<float, EPL>(c, K, lane, Gp);
+  Picks<float> P;
+  topk_stage<float, EPL>(c, K, eligible_mask<EPL>(c, Gp.kept, lane), lane, P);
+  if (P.certain && Gp.certain) {
     const float wt = pick_weight<float, EPL>(c, K, P, lane);
     if (lane < c.k) {
       ids[size_t(t) * c.k + lane] = P.id;
@@ -477,6 +531,12 @@ __global__ __launch_bounds__(256) void route_select_kernel(
 }
 
 // --------------------------------------------------------- stage 3: re-score
+// One workgroup per listed token.  Phase 1 (only when the group cut is in
+// doubt): the experts that may be among their group's largest get exact keys and
+// the groups are chosen in fp64.  Phase 2: with the groups fixed, the experts
+// whose key interval reaches the picks get exact keys and the top-k is taken in
+// fp64.  Experts outside those sets keep their fast keys: by construction they
+// cannot change either decision.
 template <int EPL, bool BF16>
 __global__ __launch_bounds__(256) void route_recheck_kernel(
     SelCfg c, int H, const void* __restrict__ x, const void* __restrict__ gate_w,
@@ -490,69 +550,102 @@ __global__ __launch_bounds__(256) void route_recheck_kernel(
   __shared__ int n_x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_list = counters[0];
-  for (int li = blockIdx.x; li < n_list; li += gridDim.x) {
-    const int t = recheck[li];
-    Keys<float, EPL> K;
-    Picks<float, EPL> P;
-    uint32_t inx = 0;
-    if (wave == 0) {
-      const float xn = c.have_norms ? sqrtf(xnorm2[t]) : 0.f;
-      fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
-      select_topk<float, EPL>(c, K, lane, P);
-      // experts whose exact key could reach the selection; all of them when the
-      // group cut itself is in doubt
-      int n = 0;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        const int e = i * 64 + lane;
-        bool in = e < c.E;
-        if (P.groups_certain) in = (P.elig >> i & 1) && (K.key[i] + K.eps[i] >= P.low);
-        const uint64_t m = __ballot(in);
-        if (in) {
-          xlist[n + __popcll(m & ((uint64_t(1) << lane) - 1))] = e;
-          inx |= 1u << i;
-        }
-        n += __popcll(m);
-      }
-      if (lane == 0) n_x = n;
-    }
-    __syncthreads();
-    const int n = n_x;
+  const size_t eb = BF16 ? 2 : 4;
+
+  // exact logits of the experts in xlist[0..n) -> zx[e]; all four wavefronts
+  auto exact_logits = [&](int t, int n) {
     for (int q = wave; q < n; q += 4) {
       const int e = xlist[q];
       double z;
       if (logits_in) {
         z = (double)logits_in[size_t(t) * c.E + e];
       } else {
-        const size_t eb = BF16 ? 2 : 4;
         z = wave_dot64<BF16>(static_cast<const char*>(x) + size_t(t) * H * eb,
                              static_cast<const char*>(gate_w) + size_t(e) * H * eb, H, lane);
       }
       if (logit_bias) z += (double)logit_bias[e];
       if (lane == 0) zx[e] = z;
     }
-    __syncthreads();
-    if (wave == 0) {
-      Keys<double, EPL> D;
+  };
+  // wavefront 0: list the experts flagged in `want` that are not yet exact
+  auto make_list = [&](uint32_t want) {
+    int n = 0;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const bool in = want >> i & 1;
+      const uint64_t m = __ballot(in);
+      if (in) xlist[n + __popcll(m & ((uint64_t(1) << lane) - 1))] = i * 64 + lane;
+      n += __popcll(m);
+    }
+    if (lane == 0) n_x = n;
+  };
+
+  for (int li = blockIdx.x; li < n_list; li += gridDim.x) {
+    const int t = recheck[li];
+    Keys<float, EPL> K;
+    Keys<double, EPL> D;
+    Groups<float> Gf;
+    Gf.kept = 0; Gf.certain = true; Gf.need = 0;
+    uint32_t exact = 0;          // slots of this lane that hold exact keys
+    uint64_t kept = 0;
+    auto adopt = [&](uint32_t want) {   // wavefront 0: pull exact logits into D
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
+        if (!(want >> i & 1)) continue;
         const int e = i * 64 + lane;
-        D.key[i] = (double)K.key[i];
-        D.sc[i] = (double)K.sc[i];
-        D.eps[i] = 0.0;
-        if (inx >> i & 1) {
-          const double z = zx[e];
-          if (c.score_fn == MOE_SCORE_SOFTMAX) {
-            D.key[i] = z; D.sc[i] = z;
-          } else {
-            const double s = 1.0 / (1.0 + exp(-z));
-            D.sc[i] = s;
-            D.key[i] = s + (select_bias ? (double)select_bias[e] : 0.0);
-          }
+        const double z = zx[e];
+        if (c.score_fn == MOE_SCORE_SOFTMAX) {
+          D.key[i] = z; D.sc[i] = z;
+        } else {
+          const double sg = 1.0 / (1.0 + exp(-z));
+          D.sc[i] = sg;
+          D.key[i] = sg + (select_bias ? (double)select_bias[e] : 0.0);
         }
       }
-      Picks<double, EPL> Q;
-      select_topk<double, EPL>(c, D, lane, Q);
+      exact |= want;
+    };
+    if (wave == 0) {
+      const float xn = c.have_norms ? sqrtf(xnorm2[t]) : 0.f;
+      fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        D.key[i] = (double)K.key[i]; D.sc[i] = (double)K.sc[i]; D.eps[i] = 0.0;
+      }
+      if (c.G > 1) group_stage<float, EPL>(c, K, lane, Gf);
+      kept = Gf.kept;
+      make_list((c.G > 1 && !Gf.certain) ? Gf.need : 0u);
+    }
+    __syncthreads();
+    int n = n_x;
+    if (n > 0) {                        // phase 1: settle the groups in fp64
+      exact_logits(t, n);
+      __syncthreads();
+      if (wave == 0) {
+        adopt(Gf.need);
+        Groups<double> Gd;
+        group_stage<double, EPL>(c, D, lane, Gd);
+        kept = Gd.kept;
+      }
+    }
+    __syncthreads();
+    uint32_t elig = 0, want = 0;
+    if (wave == 0) {                    // phase 2: candidates of the top-k
+      elig = eligible_mask<EPL>(c, kept, lane);
+      Picks<float> P;
+      topk_stage<float, EPL>(c, K, elig, lane, P);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i)
+        if ((elig >> i & 1) && !(exact >> i & 1) && (K.key[i] + K.eps[i] >= P.low)) want |= 1u << i;
+      make_list(want);
+    }
+    __syncthreads();
+    n = n_x;
+    exact_logits(t, n);
+    __syncthreads();
+    if (wave == 0) {
+      adopt(want);
+      Picks<double> Q;
+      topk_stage<double, EPL>(c, D, elig, lane, Q);
       const double wt = pick_weight<double, EPL>(c, D, Q, lane);
       if (lane < c.k) {
         ids[size_t(t) * c.k + lane] = Q.id;
