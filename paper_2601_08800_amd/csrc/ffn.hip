@@ -16,6 +16,8 @@
 // and u of the same element and the SwiGLU is applied in registers.
 // fp8 weights: e4m3 codes are widened to bf16 (exact) on the way into LDS; the
 // 128x128 block scale multiplies the fp32 partial sum of each 128-deep K block.
+#include <stdlib.h>
+
 #include "moe_internal.h"
 
 namespace moe {
@@ -283,49 +285,72 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 // NB = number of 32-row blocks of the tile that hold valid rows (1..8); a
 // compile-time constant so that the K loop is free of branches.
+//
+// K step 32 with a ring of four LDS stages (4 x 32 KB): the tiles of step s+3
+// are requested while step s is computed, so a load has about three steps to
+// arrive; `s_waitcnt vmcnt(n)` with n = the loads of the two younger steps lets
+// exactly the oldest stage complete.  LDS rows are 64 B (4 pieces of 16 B); the
+// piece index is XOR-ed with (row/4)&3, which keeps the 16 lanes that the LDS
+// serves per cycle on 16 different 16-byte columns.
+constexpr int RK = 32;                   // K step of the ring kernel
+constexpr int RSTAGES = 4;
+constexpr int RSLOTS = 256 * 4;          // 16-byte pieces per operand per stage
+
+__device__ __forceinline__ int rswz(int row, int piece) {
+  return row * 4 + (piece ^ ((row >> 2) & 3));
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+
 template <bool DUAL, int NB>
 __device__ __forceinline__ void gemm256_body(const uint16_t* __restrict__ A,
                                              const uint16_t* __restrict__ Be0,
                                              const uint16_t* __restrict__ Be1,
                                              uint16_t* __restrict__ C, int N, int K, int row0,
                                              int row1, int n0, uint4* smem) {
-  constexpr int SLOTS = 256 * 8;         // 16-byte pieces per operand buffer
-  uint4* As = smem;                      // [2][SLOTS]
-  uint4* Bs = smem + 2 * SLOTS;          // [2][SLOTS]
+  uint4* As = smem;                      // [RSTAGES][RSLOTS]
+  uint4* Bs = smem + RSTAGES * RSLOTS;   // [RSTAGES][RSLOTS]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int ksteps = K / BK;
+  const int ksteps = K / RK;
+  constexpr int NA = (NB + 1) / 2;       // A load instructions per wavefront and step
+  constexpr int LPS = NA + 4;            // loads per lane and step
 
-  // lane's place inside a group of 8 rows: row l/8, piece (l%8) ^ (l/8)
-  const int lrow = lane >> 3;
-  const int lcol = ((lane & 7) ^ lrow) * 8;
-  const uint16_t* asrc[NB];
-  const uint16_t* bsrc[8];
+  // one load instruction fills 64 consecutive slots = 16 rows; lane l sits at
+  // row l/4 and fetches the piece that belongs in slot l%4 of the swizzled row
+  const int lrow = lane >> 2;
+  const int lcol = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
+  const uint16_t* asrc[NA];
+  const uint16_t* bsrc[4];
 #pragma unroll
-  for (int q = 0; q < NB; ++q) {
-    int r = row0 + (q * 4 + wave) * 8 + lrow;
+  for (int q = 0; q < NA; ++q) {
+    int r = row0 + (q * 4 + wave) * 16 + lrow;
     r = r < row1 ? r : row1 - 1;
     asrc[q] = A + size_t(r) * K + lcol;
   }
 #pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const int rg = q * 4 + wave;
-    const int br = rg * 8 + lrow;        // LDS row of the weight tile
-    const uint16_t* base = (DUAL && q >= 4) ? Be1 : Be0;
-    int n = n0 + ((DUAL && q >= 4) ? br - 128 : br);
+  for (int q = 0; q < 4; ++q) {
+    const int br = (q * 4 + wave) * 16 + lrow;      // LDS row of the weight tile
+    const uint16_t* base = (DUAL && q >= 2) ? Be1 : Be0;
+    int n = n0 + ((DUAL && q >= 2) ? br - 128 : br);
     n = n < N ? n : N - 1;
     bsrc[q] = base + size_t(n) * K + lcol;
   }
-  auto issue = [&](int ks, int buf) {
-    const int kcol = ks * BK;
+  auto issue = [&](int ks) {
+    const int kcol = ks * RK;
+    const int st = ks & (RSTAGES - 1);
 #pragma unroll
-    for (int q = 0; q < NB; ++q)
+    for (int q = 0; q < NA; ++q)
       __builtin_amdgcn_global_load_lds((gptr_t)(asrc[q] + kcol),
-                                       (lptr_t)(As + buf * SLOTS + (q * 4 + wave) * 64), 16, 0, 0);
+                                       (lptr_t)(As + st * RSLOTS + (q * 4 + wave) * 64), 16, 0, 0);
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
+    for (int q = 0; q < 4; ++q)
       __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[q] + kcol),
-                                       (lptr_t)(Bs + buf * SLOTS + (q * 4 + wave) * 64), 16, 0, 0);
+                                       (lptr_t)(Bs + st * RSLOTS + (q * 4 + wave) * 64), 16, 0, 0);
   };
 
   f32x16 acc[NB][2];
@@ -340,52 +365,66 @@ __device__ __forceinline__ void gemm256_body(const uint16_t* __restrict__ A,
   const int brow0 = DUAL ? wave * 32 : wave * 64;
   const int brow1 = DUAL ? 128 + wave * 32 : wave * 64 + 32;
 
-  issue(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0f70);    // vmcnt(0)
-  __syncthreads();
-  for (int ks = 0; ks < ksteps; ++ks) {
-    const int buf = ks & 1;
-    if (ks + 1 < ksteps) issue(ks + 1, buf ^ 1);
-    const uint4* Ab = As + buf * SLOTS;
-    const uint4* Bb = Bs + buf * SLOTS;
-    // operand fragments are read one K sub-step ahead of the MFMAs that use them
-    uint4 fa[2][NB], fb[2][2];
-    auto read_frags = [&](int kk, int set) {
-      const int piece = kk * 2 + (lane >> 5);
-      fb[set][0] = Bb[swz(brow0 + (lane & 31), piece)];
-      fb[set][1] = Bb[swz(brow1 + (lane & 31), piece)];
+  // operand fragments are read one K sub-step ahead of the MFMAs that use them,
+  // across step boundaries too: set 0 holds sub-step 0, set 1 sub-step 1
+  uint4 fa[2][NB], fb[2][2];
+  auto read_frags = [&](int ks, int kk, int set) {
+    const uint4* Ab = As + (ks & (RSTAGES - 1)) * RSLOTS;
+    const uint4* Bb = Bs + (ks & (RSTAGES - 1)) * RSLOTS;
+    const int piece = kk * 2 + (lane >> 5);
+    fb[set][0] = Bb[rswz(brow0 + (lane & 31), piece)];
+    fb[set][1] = Bb[rswz(brow1 + (lane & 31), piece)];
 #pragma unroll
-      for (int i = 0; i < NB; ++i) fa[set][i] = Ab[swz(i * 32 + (lane & 31), piece)];
-    };
-    read_frags(0, 0);
+    for (int i = 0; i < NB; ++i) fa[set][i] = Ab[rswz(i * 32 + (lane & 31), piece)];
+  };
+  auto mfmas = [&](int set) {
+    const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[set][0]);
+    const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[set][1]);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int set = kk & 1;
-      // nothing may move across this point: the reads below belong to the
-      // next sub-step and must stay ahead of this sub-step's MFMAs
-      __builtin_amdgcn_sched_barrier(0);
-      if (kk < 3) read_frags(kk + 1, set ^ 1);
-      const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[set][0]);
-      const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[set][1]);
-#pragma unroll
-      for (int i = 0; i < NB; ++i) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, fa[set][i]);
-        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
-        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
-      }
-      if (kk < 3 && NB >= 2) {
-        // one LDS read slipped in after each of the first MFMAs
-#pragma unroll
-        for (int i = 0; i < NB + 2; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB - (NB + 2), 0);
-      }
+    for (int i = 0; i < NB; ++i) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, fa[set][i]);
+      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
+      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
     }
+  };
+  auto interleave = [&]() {   // one LDS read slipped in after each of the first MFMAs
+    if (NB >= 2) {
+#pragma unroll
+      for (int i = 0; i < NB + 2; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB - (NB + 2), 0);
+    }
+  };
+
+  issue(0);
+  if (ksteps > 1) issue(1);
+  if (ksteps > 2) issue(2);
+  // stage 0 must have landed for everyone before its fragments are read
+  if (ksteps > 2) wait_vmcnt<2 * LPS>();
+  else if (ksteps > 1) wait_vmcnt<LPS>();
+  else wait_vmcnt<0>();
+  asm volatile("s_barrier" ::: "memory");
+  read_frags(0, 0, 0);
+  for (int ks = 0; ks < ksteps; ++ks) {
+    // entering: stage ks is complete and visible, its sub-step 0 fragments are
+    // on their way.  Make stage ks+1 complete as well (the loads of step ks+2
+    // may still fly), so that its first fragments can be read under this
+    // step's MFMAs; after the barrier stage ks-1 is free for step ks+3.
+    if (ks + 2 < ksteps) wait_vmcnt<LPS>();
+    else wait_vmcnt<0>();
+    asm volatile("s_barrier" ::: "memory");
+    if (ks + 3 < ksteps) issue(ks + 3);
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // the next step's tiles have landed
-    __syncthreads();
+    read_frags(ks, 1, 1);
+    mfmas(0);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(ks + 1, 0, 0);   // after the last step this reads a stale stage; never used
+    mfmas(1);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   // D layout: lane l, register q -> row (q/4)*8 + (l/32)*4 + q%4, col l%32
@@ -406,6 +445,177 @@ __device__ __forceinline__ void gemm256_body(const uint16_t* __restrict__ A,
         }
       }
     }
+  }
+}
+
+// ---------------------------------------- MFMA GEMM, 256x256 tile, 8 wavefronts
+// Same block tile, but 512 threads: wavefront (wm, wn) = (w/4, w%4) computes rows
+// wm*128..+128 and the 64 weight rows of column block wn (DUAL: 32 gate + 32 up),
+// i.e. four 32-row blocks x two 32-column blocks = 128 accumulator registers.
+// Wavefronts w and w+4 share a SIMD, so every SIMD carries the same amount of
+// MFMA work for any tile height, and while one of them waits (LDS latency,
+// loads, barrier) the other keeps the matrix unit busy.  K step 64 (128-byte
+// rows: whole cache lines per row and load instruction), two LDS stages.
+// NBW = valid 32-row blocks of this wavefront's 128 rows (0..4).
+__device__ __forceinline__ int swz2(int row, int piece) {
+  return row * 8 + (piece ^ ((row >> 1) & 7));
+}
+
+template <bool DUAL, int NBW>
+__device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
+                                            const uint16_t* __restrict__ Be0,
+                                            const uint16_t* __restrict__ Be1,
+                                            uint16_t* __restrict__ C, int N, int K, int row0,
+                                            int row1, int n0, uint4* smem, int wave) {
+  constexpr int SLOTS = 256 * 8;
+  uint4* As = smem;                      // [2][SLOTS]
+  uint4* Bs = smem + 2 * SLOTS;          // [2][SLOTS]
+  const int lane = threadIdx.x & 63;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int ksteps = K / BK;
+  const int h = row1 - row0;
+
+  // loads: a wavefront instruction fills 64 slots = 8 rows of 128 B.  Row group
+  // rg = q*8 + wave.  Lane l -> row l/8, slot l%8 of the swizzled row, i.e. the
+  // global piece (l%8) ^ ((row>>1)&7) with row>>1 = rg*4 + (l>>4).
+  const int lrow = lane >> 3;
+  const uint16_t* asrc[4];
+  const uint16_t* bsrc[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int rg = q * 8 + wave;
+    const int piece = (lane & 7) ^ ((rg * 4 + (lane >> 4)) & 7);
+    int r = row0 + rg * 8 + lrow;
+    r = r < row1 ? r : row1 - 1;
+    asrc[q] = A + size_t(r) * K + piece * 8;
+    const int br = rg * 8 + lrow;
+    const uint16_t* base = (DUAL && br >= 128) ? Be1 : Be0;
+    int n = n0 + ((DUAL && br >= 128) ? br - 128 : br);
+    n = n < N ? n : N - 1;
+    bsrc[q] = base + size_t(n) * K + piece * 8;
+  }
+  auto issue = [&](int ks, int buf) {
+    const int kcol = ks * BK;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if ((q * 8 + wave) * 8 < h)        // skip row groups past the tile's last row
+        __builtin_amdgcn_global_load_lds((gptr_t)(asrc[q] + kcol),
+                                         (lptr_t)(As + buf * SLOTS + (q * 8 + wave) * 64), 16, 0, 0);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[q] + kcol),
+                                       (lptr_t)(Bs + buf * SLOTS + (q * 8 + wave) * 64), 16, 0, 0);
+  };
+
+  constexpr int NA = NBW > 0 ? NBW : 1;
+  f32x16 acc[NA][2];
+#pragma unroll
+  for (int i = 0; i < NA; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+
+  const int arow = wm * 128;
+  const int brow0 = DUAL ? wn * 32 : wn * 64;
+  const int brow1 = DUAL ? 128 + wn * 32 : wn * 64 + 32;
+
+  issue(0, 0);
+  wait_vmcnt<0>();
+  __syncthreads();
+  for (int ks = 0; ks < ksteps; ++ks) {
+    const int buf = ks & 1;
+    if (ks + 1 < ksteps) issue(ks + 1, buf ^ 1);
+    if constexpr (NBW > 0) {
+      const uint4* Ab = As + buf * SLOTS;
+      const uint4* Bb = Bs + buf * SLOTS;
+      uint4 fa[2][NA], fb[2][2];
+      auto read_frags = [&](int kk, int set) {
+        const int piece = kk * 2 + (lane >> 5);
+        fb[set][0] = Bb[swz2(brow0 + (lane & 31), piece)];
+        fb[set][1] = Bb[swz2(brow1 + (lane & 31), piece)];
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) fa[set][i] = Ab[swz2(arow + i * 32 + (lane & 31), piece)];
+      };
+      read_frags(0, 0);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int set = kk & 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if (kk < 3) read_frags(kk + 1, set ^ 1);
+        const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[set][0]);
+        const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[set][1]);
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+          const bf16x8 a = __builtin_bit_cast(bf16x8, fa[set][i]);
+          acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
+          acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
+        }
+        if (kk < 3 && NBW >= 2) {
+#pragma unroll
+          for (int i = 0; i < NBW + 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, 2 * NBW - (NBW + 2), 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_vmcnt<0>();                     // the next step's tiles have landed
+    __syncthreads();
+  }
+
+  if constexpr (NBW > 0) {
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int row = row0 + arow + i * 32 + (q >> 2) * 8 + (lane >> 5) * 4 + (q & 3);
+        if (row >= row1) continue;
+        if (DUAL) {
+          const int col = n0 + wn * 32 + (lane & 31);
+          if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(silu_mul(acc[i][0][q], acc[i][1][q]));
+        } else {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+            if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(acc[i][j][q]);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <bool DUAL>
+__global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
+    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
+    const uint16_t* __restrict__ B1, uint16_t* __restrict__ C, int N, int K,
+    const int32_t* __restrict__ tiles) {
+  constexpr int BN = DUAL ? 128 : 256;
+  extern __shared__ uint4 smem[];
+  const int n_ntiles = (N + BN - 1) / BN;
+  const int total = tiles[0] * n_ntiles;
+  const int per_xcd = (total + 7) >> 3;
+  const int pid = blockIdx.x;
+  const int logical = (pid & 7) * per_xcd + (pid >> 3);
+  if ((pid >> 3) >= per_xcd || logical >= total) return;
+  const int mtile = logical / n_ntiles, ntile = logical - mtile * n_ntiles;
+  const int e = tiles[1 + 3 * mtile], row0 = tiles[2 + 3 * mtile], row1 = tiles[3 + 3 * mtile];
+  const int n0 = ntile * BN;
+  const uint16_t* Be0 = B0 + size_t(e) * N * K;
+  const uint16_t* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nb = (row1 - row0 + 31) >> 5;             // valid 32-row blocks of the tile
+  int nbw = nb - (wave >> 2) * 4;                     // ... of this wavefront's half
+  nbw = nbw < 0 ? 0 : (nbw > 4 ? 4 : nbw);
+  switch (nbw) {
+    case 0: gemm8w_body<DUAL, 0>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 1: gemm8w_body<DUAL, 1>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 2: gemm8w_body<DUAL, 2>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 3: gemm8w_body<DUAL, 3>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    default: gemm8w_body<DUAL, 4>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
   }
 }
 
@@ -541,9 +751,30 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, 256,
              rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 1);
   const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
+  constexpr int lds = 4 * 256 * 8 * 16;   // A and B, double buffered: 128 KB
+  const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt * nt2 + 7) / 8 * 8;
+  static const bool use8 = getenv("MOE_GEMM_4W") == nullptr;
+  if (use8 && H % 64 == 0 && I % 64 == 0) {
+    auto k1 = ffn_gemm8w_kernel<true>;
+    auto k2 = ffn_gemm8w_kernel<false>;
+    static bool configured = false;
+    if (!configured) {
+      hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      hipFuncSetAttribute(reinterpret_cast<const void*>(k2),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+      configured = true;
+    }
+    MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
+               static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
+               static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
+    MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(g2), dim3(512), lds, s,
+               static_cast<const uint16_t*>(ws.hmid), static_cast<const uint16_t*>(w_down),
+               (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
+    return;
+  }
   auto k1 = ffn_gemm256_kernel<true>;
   auto k2 = ffn_gemm256_kernel<false>;
-  constexpr int lds = 4 * 256 * 8 * 16;   // A and B, double buffered: 128 KB
   static bool configured = false;
   if (!configured) {
     hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
@@ -552,7 +783,6 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     configured = true;
   }
-  const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt * nt2 + 7) / 8 * 8;
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(256), lds, s, static_cast<const uint16_t*>(xs),
              static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
              static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
@@ -594,7 +824,7 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
   } else if (avg <= 64) {
     if (fp8) launch_mfma_pair<64, 128, 64, 32, 256, 64, true>(MOE_FFN_ARGS);
     else launch_mfma_pair<64, 128, 64, 32, 256, 64, false>(MOE_FFN_ARGS);
-  } else if (!fp8 && H % BK == 0 && I % BK == 0) {
+  } else if (!fp8 && H % 32 == 0 && I % 32 == 0) {
     launch_mfma256(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
   } else {
     if (fp8) launch_mfma_pair<128, 64, 64, 32, 128, 64, true>(MOE_FFN_ARGS);
