@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--workload", default="c2p", choices=list(DESCR))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one GPU's share on one GPU; --gpus %d is not supported "
@@ -90,6 +92,14 @@ def main():
     x = to_device(x_np)
     forced = None if forced_np is None else (to_device(forced_np[0]), to_device(forced_np[1]))
 
+    if args.calibration_copy:
+        # a copy of known size: rocprofv3 FETCH_SIZE / WRITE_SIZE of this dispatch
+        # give the factor that turns the counters into bytes
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         L.forward(x, forced)
     torch.cuda.synchronize()

@@ -2,12 +2,12 @@
 //
 // A stable counting sort of the local assignments by expert, with no atomics
 // anywhere (so the permutation is unique and repeatable):
-//   1. hist    per sub-chunk of 256 consecutive assignments and per local
-//              expert, count by comparison (a thread per pair, no atomics)
-//   2. scan    per expert an exclusive scan over sub-chunks, then an exclusive
-//              scan over experts -> counts, offsets, per-pair start positions
-//   3. scatter every (sub-chunk, expert) pair walks its 256 ids in order and
-//              writes perm / inv from its start position
+//   1. hist    one wavefront per sub-chunk of 64 consecutive assignments counts
+//              them per local expert with ballots (no atomics)
+//   2. scan    per expert (one wavefront each) an exclusive scan over the
+//              sub-chunks -> counts; then offsets = exclusive scan over experts
+//   3. scatter the same ballots give every assignment its rank inside its
+//              sub-chunk; position = offsets[e] + start of sub-chunk + rank
 //   4. gather  one wavefront per token reads the row ONCE (16 B per lane,
 //              coalesced) and writes it to each of its local positions
 #include "moe_internal.h"
@@ -16,107 +16,107 @@ namespace moe {
 
 namespace {
 
-constexpr int kMaxLocalExperts = 512;
+constexpr int kSub = 64;   // assignments per histogram column: one wavefront
 
-constexpr int kSub = 256;                         // assignments per histogram row
-constexpr int kSubsPerBlock = kDispatchChunk / kSub;
+__device__ __forceinline__ uint64_t lanemask_lt() {
+  return (uint64_t(1) << (threadIdx.x & 63)) - 1;
+}
 
-// hist[sub][e] = number of assignments of sub-chunk `sub` (256 consecutive
-// flat assignments) that go to local expert e.  A workgroup stages 1024 ids in
-// LDS; each thread owns (sub-chunk, expert) pairs and counts by comparison, so
-// no atomics are needed.  MODE 1 walks the same pairs again, now with the
-// start position of each pair known, and writes perm / inv in order.
+// One wavefront per sub-chunk of 64 consecutive flat assignments.  The lanes
+// that go to the same local expert find each other with ballots (one round per
+// distinct expert present), which yields the count per expert (MODE 0) or the
+// rank of every assignment among its expert's assignments of the sub-chunk
+// (MODE 1) without atomics.  hist is [E_loc][n_sub].
 template <int MODE>
 __global__ __launch_bounds__(256) void dispatch_index_kernel(
-    const int32_t* __restrict__ ids, int A, int e_lo, int E_loc, int32_t* __restrict__ hist,
-    int32_t* __restrict__ perm, int32_t* __restrict__ inv) {
-  __shared__ int32_t sid[kDispatchChunk];
-  const int base = blockIdx.x * kDispatchChunk;
-  for (int i = threadIdx.x; i < kDispatchChunk; i += 256) {
-    const int a = base + i;
-    int e = -1;
-    if (a < A) {
-      e = ids[a] - e_lo;
-      if (e < 0 || e >= E_loc) {
-        e = -1;
-        if (MODE == 1) inv[a] = -1;
-      }
+    const int32_t* __restrict__ ids, int A, int e_lo, int E_loc, int n_sub,
+    int32_t* __restrict__ hist, const int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
+    int32_t* __restrict__ inv) {
+  const int lane = threadIdx.x & 63;
+  const int sub = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (sub >= n_sub) return;
+  const int a = sub * kSub + lane;
+  int e = -1;
+  if (a < A) {
+    e = ids[a] - e_lo;
+    if (e < 0 || e >= E_loc) {
+      e = -1;
+      if (MODE == 1) inv[a] = -1;
     }
-    sid[i] = e;
   }
-  __syncthreads();
-  for (int pair = threadIdx.x; pair < kSubsPerBlock * E_loc; pair += 256) {
-    const int sub = pair / E_loc, e = pair - sub * E_loc;
-    const int32_t* row = sid + sub * kSub;
-    const size_t h = (size_t(blockIdx.x) * kSubsPerBlock + sub) * E_loc + e;
+  uint64_t present[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // experts seen in this sub-chunk (E_loc <= 512)
+  uint64_t todo = __ballot(e >= 0);
+  while (todo) {                               // one round per distinct expert
+    const int leader = __ffsll((unsigned long long)todo) - 1;
+    const int e0 = __shfl(e, leader);
+    const uint64_t m = __ballot(e == e0);
     if (MODE == 0) {
-      int n = 0;
-#pragma unroll 8
-      for (int i = 0; i < kSub; ++i) n += (row[i] == e);
-      hist[h] = n;
-    } else {
-      int pos = hist[h];
-      const int a0 = base + sub * kSub;
-      for (int i = 0; i < kSub; ++i) {
-        if (row[i] == e) {
-          perm[pos] = a0 + i;
-          inv[a0 + i] = pos;
-          ++pos;
-        }
-      }
+      if (lane == leader) hist[size_t(e0) * n_sub + sub] = __popcll(m);
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if ((e0 >> 6) == q) present[q] |= uint64_t(1) << (e0 & 63);
+    } else if (e == e0) {
+      const int pos = hist[size_t(e0) * n_sub + sub] + offsets[e0] + __popcll(m & lanemask_lt());
+      perm[pos] = a;
+      inv[a] = pos;
+    }
+    todo &= ~m;
+  }
+  if (MODE == 0) {                             // the other experts have no assignment here
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int x = q * 64 + lane;
+      if (x < E_loc && !(present[q] >> lane & 1)) hist[size_t(x) * n_sub + sub] = 0;
     }
   }
 }
 
-// Single block.  hist[sub][e] (counts) -> start position of sub-chunk `sub`'s
-// first assignment of expert e; counts[e]; offsets = exclusive scan of counts.
-// Thread (e, seg) sums a contiguous segment of sub-chunks, the segment totals
-// are scanned in LDS, then each thread rewrites its segment as running starts.
-__global__ __launch_bounds__(256) void dispatch_scan_kernel(int32_t* __restrict__ hist, int n_sub,
-                                                           int E_loc, int32_t* __restrict__ counts,
-                                                           int32_t* __restrict__ offsets) {
-  __shared__ int32_t seg_tot[256];
-  __shared__ int32_t tot[kMaxLocalExperts + 1];
-  const int segs = E_loc >= 256 ? 1 : 256 / E_loc;
-  const int per = (n_sub + segs - 1) / segs;
-  for (int e0 = 0; e0 < E_loc; e0 += 256) {
-    const int e = e0 + int(threadIdx.x) % (E_loc < 256 ? E_loc : 256);
-    const int seg = int(threadIdx.x) / (E_loc < 256 ? E_loc : 256);
-    const bool on = seg < segs && e < E_loc;
-    const int s0 = seg * per, s1 = (s0 + per < n_sub) ? s0 + per : n_sub;
-    int sum = 0;
-    if (on)
-      for (int sb = s0; sb < s1; ++sb) sum += hist[size_t(sb) * E_loc + e];
-    seg_tot[threadIdx.x] = on ? sum : 0;
-    __syncthreads();
-    int before = 0;
-    if (on) {
-      const int stride = E_loc < 256 ? E_loc : 256;
-      for (int q = 0; q < seg; ++q) before += seg_tot[q * stride + (e - e0)];
-      int all = before;
-      for (int q = seg; q < segs; ++q) all += seg_tot[q * stride + (e - e0)];
-      if (seg == 0) { tot[e] = all; counts[e] = all; }
-      int run = before;
-      for (int sb = s0; sb < s1; ++sb) {
-        const int c = hist[size_t(sb) * E_loc + e];
-        hist[size_t(sb) * E_loc + e] = run;
-        run += c;
-      }
-    }
-    __syncthreads();
+// One wavefront per local expert: exclusive scan of the expert's row of counts
+// (lane l owns a contiguous run of sub-chunks), counts[e] = the row's total.
+__global__ __launch_bounds__(64) void dispatch_scan_kernel(int32_t* __restrict__ hist, int n_sub,
+                                                          int32_t* __restrict__ counts) {
+  const int lane = threadIdx.x, e = blockIdx.x;
+  int32_t* row = hist + size_t(e) * n_sub;
+  const int per = (n_sub + 63) / 64;
+  const int s0 = lane * per, s1 = (s0 + per < n_sub) ? s0 + per : n_sub;
+  int sum = 0;
+  for (int sb = s0; sb < s1; ++sb) sum += row[sb];
+  int incl = sum;                               // inclusive scan over lanes
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
   }
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int e = 0; e < E_loc; ++e) {
-      const int c = tot[e];
-      tot[e] = run;
-      offsets[e] = run;
-      run += c;
-    }
-    offsets[E_loc] = run;
+  int run = incl - sum;
+  for (int sb = s0; sb < s1; ++sb) {
+    const int c = row[sb];
+    row[sb] = run;
+    run += c;
   }
-  __syncthreads();
-  for (int i = threadIdx.x; i < n_sub * E_loc; i += blockDim.x) hist[i] += tot[i % E_loc];
+  if (lane == 63) counts[e] = incl;
+}
+
+// One wavefront: offsets = exclusive scan of counts (E_loc <= 512).
+__global__ __launch_bounds__(64) void dispatch_offsets_kernel(const int32_t* __restrict__ counts,
+                                                             int E_loc,
+                                                             int32_t* __restrict__ offsets) {
+  const int lane = threadIdx.x;
+  const int per = (E_loc + 63) / 64;
+  const int e0 = lane * per, e1 = (e0 + per < E_loc) ? e0 + per : E_loc;
+  int sum = 0;
+  for (int e = e0; e < e1; ++e) sum += counts[e];
+  int incl = sum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
+  }
+  int run = incl - sum;
+  for (int e = e0; e < e1; ++e) {
+    offsets[e] = run;
+    run += counts[e];
+  }
+  if (lane == 63) offsets[E_loc] = incl;
 }
 
 // One wavefront per token: read the row once, write it to every local position.
@@ -164,12 +164,16 @@ hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int3
   const int k = c.top_k;
   const int A = T * k;
   const int E_loc = c.expert_hi - c.expert_lo;
-  MOE_LAUNCH(MOE_K_DISPATCH_HIST, dispatch_index_kernel<0>, dim3(ws.n_blocks), dim3(256), 0, s, ids, A,
-                     c.expert_lo, E_loc, ws.block_hist, perm, inv);
-  MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_scan_kernel, dim3(1), dim3(256), 0, s, ws.block_hist, ws.n_blocks * kSubsPerBlock,
-                     E_loc, counts, offsets);
-  MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_index_kernel<1>, dim3(ws.n_blocks), dim3(256), 0, s, ids, A,
-                     c.expert_lo, E_loc, ws.block_hist, perm, inv);
+  const int n_sub = (A + kSub - 1) / kSub;
+  const dim3 grid_idx((n_sub + 3) / 4), block_idx(256);
+  MOE_LAUNCH(MOE_K_DISPATCH_HIST, dispatch_index_kernel<0>, grid_idx, block_idx, 0, s, ids, A,
+             c.expert_lo, E_loc, n_sub, ws.block_hist, (const int32_t*)nullptr, perm, inv);
+  MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_scan_kernel, dim3(E_loc), dim3(64), 0, s, ws.block_hist,
+             n_sub, counts);
+  MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_offsets_kernel, dim3(1), dim3(64), 0, s, counts, E_loc,
+             offsets);
+  MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_index_kernel<1>, grid_idx, block_idx, 0, s, ids, A,
+             c.expert_lo, E_loc, n_sub, ws.block_hist, offsets, perm, inv);
   const int row16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
   MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_gather_kernel<8>, dim3((T + 3) / 4), dim3(256), 0, s,
                      static_cast<const uint4*>(x), inv, static_cast<uint4*>(xs), T, k, row16);

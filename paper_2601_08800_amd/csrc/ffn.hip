@@ -16,8 +16,6 @@
 // and u of the same element and the SwiGLU is applied in registers.
 // fp8 weights: e4m3 codes are widened to bf16 (exact) on the way into LDS; the
 // 128x128 block scale multiplies the fp32 partial sum of each 128-deep K block.
-#include <stdlib.h>
-
 #include "moe_internal.h"
 
 namespace moe {
@@ -41,7 +39,9 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 }
 
 // ------------------------------------------------------------- tile table
-// tiles[0] = number of M tiles; then (expert, first row, end row) per tile.
+// tiles[0] = number of M tiles; then per tile a record (expert, first row, end
+// row, index of the expert's first tile, number of tiles of the expert).
+constexpr int kTileRec = 5;
 // `balance`: an expert's rows are cut into ceil(M/bm) tiles of equal height
 // (rounded up to 32 rows) instead of full tiles plus a short tail.
 __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restrict__ offsets,
@@ -56,14 +56,28 @@ __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restric
     off[e] = o > rows_capacity ? rows_capacity : o;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int e = 0; e < n_experts; ++e) {
-      const int lo = off[e], hi = off[e + 1];
-      start[e] = run;
-      run += hi > lo ? (hi - lo + bm - 1) / bm : 0;
+  if (threadIdx.x < 64) {                 // one wavefront scans the tile counts
+    const int lane = threadIdx.x;
+    const int per = (n_experts + 63) / 64;
+    const int e0 = lane * per, e1 = (e0 + per < n_experts) ? e0 + per : n_experts;
+    int sum = 0;
+    for (int e = e0; e < e1; ++e) {
+      const int m = off[e + 1] - off[e];
+      sum += m > 0 ? (m + bm - 1) / bm : 0;
     }
-    tiles[0] = run < max_tiles ? run : max_tiles;
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o);
+      if (lane >= o) incl += v;
+    }
+    int run = incl - sum;
+    for (int e = e0; e < e1; ++e) {
+      const int m = off[e + 1] - off[e];
+      start[e] = run;
+      run += m > 0 ? (m + bm - 1) / bm : 0;
+    }
+    if (lane == 63) tiles[0] = incl < max_tiles ? incl : max_tiles;
   }
   __syncthreads();
   for (int e = threadIdx.x; e < n_experts; e += blockDim.x) {
@@ -75,9 +89,11 @@ __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restric
       step = (((hi - lo + nt - 1) / nt) + 31) / 32 * 32;
     }
     for (int r = lo; r < hi && t < max_tiles; r += step, ++t) {
-      tiles[1 + 3 * t] = e;
-      tiles[2 + 3 * t] = r;
-      tiles[3 + 3 * t] = (r + step < hi) ? r + step : hi;
+      tiles[1 + kTileRec * t] = e;
+      tiles[2 + kTileRec * t] = r;
+      tiles[3 + kTileRec * t] = (r + step < hi) ? r + step : hi;
+      tiles[4 + kTileRec * t] = start[e];
+      tiles[5 + kTileRec * t] = (hi - lo + step - 1) / step;
     }
   }
 }
@@ -106,7 +122,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
   const int n_ntiles = (N + BN - 1) / BN;
   const int mtile = blockIdx.x / n_ntiles, ntile = blockIdx.x % n_ntiles;
   if (mtile >= tiles[0]) return;
-  const int e = tiles[1 + 3 * mtile], row0 = tiles[2 + 3 * mtile], row1 = tiles[3 + 3 * mtile];
+  const int e = tiles[1 + kTileRec * mtile], row0 = tiles[2 + kTileRec * mtile],
+            row1 = tiles[3 + kTileRec * mtile];
   const int n0 = ntile * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -269,36 +286,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
     }
 }
 
-// ------------------------------------------------- MFMA GEMM, 256-row tiles
-// Prefill-sized groups: block tile 256 rows x 256 weight rows (DUAL: 128 gate
-// + the matching 128 up rows), K step 64, four wavefronts side by side along N
-// so that each one spans all 256 rows: a short tile (ragged group tail) then
-// idles no wavefront, it just skips the 32-row MFMA blocks past its last row.
-// Operands go global -> LDS directly (16 B per lane, no register staging); the
-// per-lane global address is permuted so that the linear LDS write of a
-// wavefront lands in the XOR-swizzled layout the MFMA operand reads expect.
-// Workgroup ids are remapped so that each XCD (own L2) walks a contiguous run
-// of tiles: neighbours in that run share the activation panel (same M tile)
-// and, one group of N tiles later, the expert's weight panels.
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
-
-// NB = number of 32-row blocks of the tile that hold valid rows (1..8); a
-// compile-time constant so that the K loop is free of branches.
-//
-// K step 32 with a ring of four LDS stages (4 x 32 KB): the tiles of step s+3
-// are requested while step s is computed, so a load has about three steps to
-// arrive; `s_waitcnt vmcnt(n)` with n = the loads of the two younger steps lets
-// exactly the oldest stage complete.  LDS rows are 64 B (4 pieces of 16 B); the
-// piece index is XOR-ed with (row/4)&3, which keeps the 16 lanes that the LDS
-// serves per cycle on 16 different 16-byte columns.
-constexpr int RK = 32;                   // K step of the ring kernel
-constexpr int RSTAGES = 4;
-constexpr int RSLOTS = 256 * 4;          // 16-byte pieces per operand per stage
-
-__device__ __forceinline__ int rswz(int row, int piece) {
-  return row * 4 + (piece ^ ((row >> 2) & 3));
-}
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -306,152 +295,19 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <bool DUAL, int NB>
-__device__ __forceinline__ void gemm256_body(const uint16_t* __restrict__ A,
-                                             const uint16_t* __restrict__ Be0,
-                                             const uint16_t* __restrict__ Be1,
-                                             uint16_t* __restrict__ C, int N, int K, int row0,
-                                             int row1, int n0, uint4* smem) {
-  uint4* As = smem;                      // [RSTAGES][RSLOTS]
-  uint4* Bs = smem + RSTAGES * RSLOTS;   // [RSTAGES][RSLOTS]
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int ksteps = K / RK;
-  constexpr int NA = (NB + 1) / 2;       // A load instructions per wavefront and step
-  constexpr int LPS = NA + 4;            // loads per lane and step
-
-  // one load instruction fills 64 consecutive slots = 16 rows; lane l sits at
-  // row l/4 and fetches the piece that belongs in slot l%4 of the swizzled row
-  const int lrow = lane >> 2;
-  const int lcol = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
-  const uint16_t* asrc[NA];
-  const uint16_t* bsrc[4];
-#pragma unroll
-  for (int q = 0; q < NA; ++q) {
-    int r = row0 + (q * 4 + wave) * 16 + lrow;
-    r = r < row1 ? r : row1 - 1;
-    asrc[q] = A + size_t(r) * K + lcol;
-  }
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int br = (q * 4 + wave) * 16 + lrow;      // LDS row of the weight tile
-    const uint16_t* base = (DUAL && q >= 2) ? Be1 : Be0;
-    int n = n0 + ((DUAL && q >= 2) ? br - 128 : br);
-    n = n < N ? n : N - 1;
-    bsrc[q] = base + size_t(n) * K + lcol;
-  }
-  auto issue = [&](int ks) {
-    const int kcol = ks * RK;
-    const int st = ks & (RSTAGES - 1);
-#pragma unroll
-    for (int q = 0; q < NA; ++q)
-      __builtin_amdgcn_global_load_lds((gptr_t)(asrc[q] + kcol),
-                                       (lptr_t)(As + st * RSLOTS + (q * 4 + wave) * 64), 16, 0, 0);
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-      __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[q] + kcol),
-                                       (lptr_t)(Bs + st * RSLOTS + (q * 4 + wave) * 64), 16, 0, 0);
-  };
-
-  f32x16 acc[NB][2];
-#pragma unroll
-  for (int i = 0; i < NB; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-
-  // LDS rows of this wavefront's two 32-column blocks of the weight tile
-  const int brow0 = DUAL ? wave * 32 : wave * 64;
-  const int brow1 = DUAL ? 128 + wave * 32 : wave * 64 + 32;
-
-  // operand fragments are read one K sub-step ahead of the MFMAs that use them,
-  // across step boundaries too: set 0 holds sub-step 0, set 1 sub-step 1
-  uint4 fa[2][NB], fb[2][2];
-  auto read_frags = [&](int ks, int kk, int set) {
-    const uint4* Ab = As + (ks & (RSTAGES - 1)) * RSLOTS;
-    const uint4* Bb = Bs + (ks & (RSTAGES - 1)) * RSLOTS;
-    const int piece = kk * 2 + (lane >> 5);
-    fb[set][0] = Bb[rswz(brow0 + (lane & 31), piece)];
-    fb[set][1] = Bb[rswz(brow1 + (lane & 31), piece)];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) fa[set][i] = Ab[rswz(i * 32 + (lane & 31), piece)];
-  };
-  auto mfmas = [&](int set) {
-    const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[set][0]);
-    const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[set][1]);
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const bf16x8 a = __builtin_bit_cast(bf16x8, fa[set][i]);
-      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
-      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
-    }
-  };
-  auto interleave = [&]() {   // one LDS read slipped in after each of the first MFMAs
-    if (NB >= 2) {
-#pragma unroll
-      for (int i = 0; i < NB + 2; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB - (NB + 2), 0);
-    }
-  };
-
-  issue(0);
-  if (ksteps > 1) issue(1);
-  if (ksteps > 2) issue(2);
-  // stage 0 must have landed for everyone before its fragments are read
-  if (ksteps > 2) wait_vmcnt<2 * LPS>();
-  else if (ksteps > 1) wait_vmcnt<LPS>();
-  else wait_vmcnt<0>();
-  asm volatile("s_barrier" ::: "memory");
-  read_frags(0, 0, 0);
-  for (int ks = 0; ks < ksteps; ++ks) {
-    // entering: stage ks is complete and visible, its sub-step 0 fragments are
-    // on their way.  Make stage ks+1 complete as well (the loads of step ks+2
-    // may still fly), so that its first fragments can be read under this
-    // step's MFMAs; after the barrier stage ks-1 is free for step ks+3.
-    if (ks + 2 < ksteps) wait_vmcnt<LPS>();
-    else wait_vmcnt<0>();
-    asm volatile("s_barrier" ::: "memory");
-    if (ks + 3 < ksteps) issue(ks + 3);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(ks, 1, 1);
-    mfmas(0);
-    interleave();
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(ks + 1, 0, 0);   // after the last step this reads a stale stage; never used
-    mfmas(1);
-    interleave();
-    __builtin_amdgcn_sched_barrier(0);
-  }
-
-  // D layout: lane l, register q -> row (q/4)*8 + (l/32)*4 + q%4, col l%32
-#pragma unroll
-  for (int i = 0; i < NB; ++i) {
-#pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      const int row = row0 + i * 32 + (q >> 2) * 8 + (lane >> 5) * 4 + (q & 3);
-      if (row >= row1) continue;
-      if (DUAL) {
-        const int col = n0 + wave * 32 + (lane & 31);
-        if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(silu_mul(acc[i][0][q], acc[i][1][q]));
-      } else {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int col = n0 + wave * 64 + j * 32 + (lane & 31);
-          if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(acc[i][j][q]);
-        }
-      }
-    }
-  }
-}
-
 // ---------------------------------------- MFMA GEMM, 256x256 tile, 8 wavefronts
-// Same block tile, but 512 threads: wavefront (wm, wn) = (w/4, w%4) computes rows
-// wm*128..+128 and the 64 weight rows of column block wn (DUAL: 32 gate + 32 up),
-// i.e. four 32-row blocks x two 32-column blocks = 128 accumulator registers.
+// Prefill-sized groups.  Block tile 256 rows x 256 weight rows (DUAL: 128 gate +
+// the matching 128 up rows), 512 threads: wavefront (wm, wn) = (w/4, w%4) computes
+// rows wm*128..+128 and the 64 weight rows of column block wn (DUAL: 32 gate + 32
+// up), i.e. four 32-row blocks x two 32-column blocks = 128 accumulator registers.
+// Operands go global -> LDS directly (16 B per lane, no register staging); the
+// per-lane global address is permuted so that the linear LDS write of a
+// wavefront lands in the XOR-swizzled layout the MFMA operand reads expect
+// (piece ^ (row/2)&7: the 16 lanes the LDS serves per cycle hit 16 different
+// 16-byte columns).  Operand fragments are read one K sub-step ahead of the
+// MFMAs that consume them.  Workgroup ids are remapped so that each XCD (own L2)
+// walks a contiguous run of tiles, M tiles of one expert first: neighbours
+// share the expert's weight panel and, one run later, the activation panel.
 // Wavefronts w and w+4 share a SIMD, so every SIMD carries the same amount of
 // MFMA work for any tile height, and while one of them waits (LDS latency,
 // loads, barrier) the other keeps the matrix unit busy.  K step 64 (128-byte
@@ -592,7 +448,7 @@ template <bool DUAL>
 __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
     const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
     const uint16_t* __restrict__ B1, uint16_t* __restrict__ C, int N, int K,
-    const int32_t* __restrict__ tiles) {
+    const int32_t* __restrict__ tiles, int m_fastest) {
   constexpr int BN = DUAL ? 128 : 256;
   extern __shared__ uint4 smem[];
   const int n_ntiles = (N + BN - 1) / BN;
@@ -601,8 +457,17 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
   const int pid = blockIdx.x;
   const int logical = (pid & 7) * per_xcd + (pid >> 3);
   if ((pid >> 3) >= per_xcd || logical >= total) return;
-  const int mtile = logical / n_ntiles, ntile = logical - mtile * n_ntiles;
-  const int e = tiles[1 + 3 * mtile], row0 = tiles[2 + 3 * mtile], row1 = tiles[3 + 3 * mtile];
+  int mtile = logical / n_ntiles, ntile = logical - mtile * n_ntiles;
+  if (m_fastest) {
+    // inside an expert's block of tiles walk the M tiles first, so that the
+    // workgroups that share a weight panel are neighbours
+    const int first = tiles[4 + kTileRec * mtile], cnt = tiles[5 + kTileRec * mtile];
+    const int local = logical - first * n_ntiles;
+    ntile = local / cnt;
+    mtile = first + (local - ntile * cnt);
+  }
+  const int e = tiles[1 + kTileRec * mtile], row0 = tiles[2 + kTileRec * mtile],
+            row1 = tiles[3 + kTileRec * mtile];
   const int n0 = ntile * BN;
   const uint16_t* Be0 = B0 + size_t(e) * N * K;
   const uint16_t* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
@@ -616,36 +481,6 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
     case 2: gemm8w_body<DUAL, 2>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
     case 3: gemm8w_body<DUAL, 3>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
     default: gemm8w_body<DUAL, 4>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-  }
-}
-
-template <bool DUAL>
-__global__ __launch_bounds__(256) void ffn_gemm256_kernel(
-    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
-    const uint16_t* __restrict__ B1, uint16_t* __restrict__ C, int N, int K,
-    const int32_t* __restrict__ tiles) {
-  constexpr int BN = DUAL ? 128 : 256;   // output columns per block
-  extern __shared__ uint4 smem[];
-  const int n_ntiles = (N + BN - 1) / BN;
-  const int total = tiles[0] * n_ntiles;
-  const int per_xcd = (total + 7) >> 3;
-  const int pid = blockIdx.x;
-  const int logical = (pid & 7) * per_xcd + (pid >> 3);
-  if ((pid >> 3) >= per_xcd || logical >= total) return;
-  const int mtile = logical / n_ntiles, ntile = logical - mtile * n_ntiles;
-  const int e = tiles[1 + 3 * mtile], row0 = tiles[2 + 3 * mtile], row1 = tiles[3 + 3 * mtile];
-  const int n0 = ntile * BN;
-  const uint16_t* Be0 = B0 + size_t(e) * N * K;
-  const uint16_t* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
-  switch ((row1 - row0 + 31) >> 5) {     // valid 32-row blocks of this tile
-    case 1: gemm256_body<DUAL, 1>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
-    case 2: gemm256_body<DUAL, 2>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
-    case 3: gemm256_body<DUAL, 3>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
-    case 4: gemm256_body<DUAL, 4>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
-    case 5: gemm256_body<DUAL, 5>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
-    case 6: gemm256_body<DUAL, 6>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
-    case 7: gemm256_body<DUAL, 7>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
-    default: gemm256_body<DUAL, 8>(A, Be0, Be1, C, N, K, row0, row1, n0, smem); break;
   }
 }
 
@@ -665,7 +500,8 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
   const int n_ntiles = (N + TB - 1) / TB;
   const int mtile = blockIdx.x / n_ntiles, ntile = blockIdx.x % n_ntiles;
   if (mtile >= tiles[0]) return;
-  const int e = tiles[1 + 3 * mtile], row0 = tiles[2 + 3 * mtile], row1 = tiles[3 + 3 * mtile];
+  const int e = tiles[1 + kTileRec * mtile], row0 = tiles[2 + kTileRec * mtile],
+            row1 = tiles[3 + kTileRec * mtile];
   const int n0 = ntile * TB;
   const float* Be0 = B0 + size_t(e) * N * K;
   const float* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
@@ -753,29 +589,9 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
   constexpr int lds = 4 * 256 * 8 * 16;   // A and B, double buffered: 128 KB
   const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt * nt2 + 7) / 8 * 8;
-  static const bool use8 = getenv("MOE_GEMM_4W") == nullptr;
-  if (use8 && H % 64 == 0 && I % 64 == 0) {
-    auto k1 = ffn_gemm8w_kernel<true>;
-    auto k2 = ffn_gemm8w_kernel<false>;
-    static bool configured = false;
-    if (!configured) {
-      hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-      hipFuncSetAttribute(reinterpret_cast<const void*>(k2),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-      configured = true;
-    }
-    MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
-               static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
-               static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
-    MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(g2), dim3(512), lds, s,
-               static_cast<const uint16_t*>(ws.hmid), static_cast<const uint16_t*>(w_down),
-               (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
-    return;
-  }
-  auto k1 = ffn_gemm256_kernel<true>;
-  auto k2 = ffn_gemm256_kernel<false>;
-  static bool configured = false;
+  auto k1 = ffn_gemm8w_kernel<true>;
+  auto k2 = ffn_gemm8w_kernel<false>;
+  static bool configured = false;     // LDS above 64 KB must be opted into, once per kernel
   if (!configured) {
     hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -783,12 +599,12 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
                         hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     configured = true;
   }
-  MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(256), lds, s, static_cast<const uint16_t*>(xs),
+  MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
              static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
-             static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
-  MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(g2), dim3(256), lds, s,
+             static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
+  MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(g2), dim3(512), lds, s,
              static_cast<const uint16_t*>(ws.hmid), static_cast<const uint16_t*>(w_down),
-             (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
+             (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles, 1);
 }
 
 }  // namespace
@@ -824,7 +640,7 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
   } else if (avg <= 64) {
     if (fp8) launch_mfma_pair<64, 128, 64, 32, 256, 64, true>(MOE_FFN_ARGS);
     else launch_mfma_pair<64, 128, 64, 32, 256, 64, false>(MOE_FFN_ARGS);
-  } else if (!fp8 && H % 32 == 0 && I % 32 == 0) {
+  } else if (!fp8 && H % BK == 0 && I % BK == 0) {
     launch_mfma256(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
   } else {
     if (fp8) launch_mfma_pair<128, 64, 64, 32, 128, 64, true>(MOE_FFN_ARGS);

@@ -55,9 +55,9 @@ RouteWs carve_route(void* ws, int T, int E) {
 DispatchWs carve_dispatch(void* ws, int T, int k, int E_loc) {
   DispatchWs d;
   size_t A = size_t(T) * k;
-  d.n_blocks = int((A + kDispatchChunk - 1) / kDispatchChunk);
+  d.n_blocks = int((A + kDispatchChunk - 1) / kDispatchChunk);   // sub-chunks of 64 assignments
   d.block_hist = static_cast<int32_t*>(ws);
-  d.bytes = align_up(size_t(d.n_blocks) * (kDispatchChunk / 256) * E_loc * 4);
+  d.bytes = align_up(size_t(d.n_blocks) * E_loc * 4);
   return d;
 }
 
@@ -66,7 +66,7 @@ FfnWs carve_ffn(void* ws, int rows_capacity, int n_experts, int I_loc, int abyte
   char* p = static_cast<char*>(ws);
   f.max_tiles = rows_capacity / kMaxTileRows + n_experts + 1;
   size_t off = 0;
-  f.tiles = reinterpret_cast<int32_t*>(p + off); off += align_up(size_t(1 + 3 * f.max_tiles) * 4 + 12);
+  f.tiles = reinterpret_cast<int32_t*>(p + off); off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
   f.hmid = p + off;                              off += align_up(size_t(rows_capacity) * I_loc * abytes);
   f.bytes = off;
   return f;

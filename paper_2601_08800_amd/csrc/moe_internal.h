@@ -30,10 +30,11 @@ struct RouteWs {
 RouteWs carve_route(void* ws, int T, int E);
 
 // dispatch
-constexpr int kDispatchChunk = 1024;          // assignments per histogram block
+constexpr int kDispatchChunk = 64;            // assignments per histogram column (one wavefront)
 struct DispatchWs {
-  int32_t* block_hist; // [n_blocks * 4 sub-chunks, E_loc] -> after the scan: start
-                       // position of the sub-chunk's first assignment of each expert
+  int32_t* block_hist; // [E_loc, n_blocks] counts per expert and sub-chunk of 64
+                       // assignments -> after the scan: start of the sub-chunk's
+                       // run inside the expert's segment
   int n_blocks;
   size_t bytes;
 };
