@@ -271,3 +271,37 @@ def test_fp8_block_quantiser():
     w2[0, 0] = 448.0
     c2, s2 = gen.quantize_e4m3_block128(w2)
     assert s2[0, 0] == 1.0 and np.array_equal(oracle.decode(c2), w2)
+
+
+def test_frozen_tiny_layer_and_hand_check():
+    """The stored fixture (written by tests/golden/make_golden.py from the oracle
+    alone) still matches, and its first token is re-derived by hand here."""
+    import os
+    import sys
+    gdir = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    sys.path.insert(0, gdir)
+    import make_golden
+    ids, w, offsets, perm, out = make_golden.compute()
+    rec = {}
+    for line in open(os.path.join(gdir, "tiny_layer.txt")):
+        if not line.startswith("#"):
+            key, *vals = line.split()
+            rec[key] = vals
+    assert list(map(int, rec["ids"])) == list(ids.ravel())
+    assert list(map(int, rec["offsets"])) == list(offsets)
+    assert list(map(int, rec["perm"])) == list(perm)
+    np.testing.assert_allclose(np.array(rec["w"], np.float64), w.ravel(), rtol=1e-7)
+    np.testing.assert_allclose(np.array(rec["out"], np.float64), out.ravel(), rtol=1e-6, atol=1e-9)
+    # token 0 by hand: logits, top-2, softmax over the two, two tiny MLPs
+    x, gw, W, k = make_golden.tiny_inputs()
+    z = [float(np.dot(x[0].astype(np.float64), gw[e].astype(np.float64))) for e in range(4)]
+    top = sorted(range(4), key=lambda e: (-z[e], e))[:2]
+    assert top == list(ids[0])
+    p = np.exp(np.array([z[e] for e in top]) - max(z))
+    p /= p.sum()
+    acc = np.zeros(4)
+    for e, pw in zip(top, p):
+        g = W["w_gate"][e].astype(np.float64) @ x[0]
+        u = W["w_up"][e].astype(np.float64) @ x[0]
+        acc += np.float32(pw).astype(np.float64) * (W["w_down"][e].astype(np.float64) @ (g / (1 + np.exp(-g)) * u))
+    np.testing.assert_allclose(out[0], acc, rtol=1e-6, atol=1e-9)
