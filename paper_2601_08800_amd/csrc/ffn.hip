@@ -317,50 +317,87 @@ __device__ __forceinline__ int swz2(int row, int piece) {
   return row * 8 + (piece ^ ((row >> 1) & 7));
 }
 
-template <bool DUAL, int NBW>
+// NB = valid 32-row blocks of the tile (1..8), WM = which half of the rows this
+// wavefront computes; both compile-time so the K loop has no branches.  A stage
+// holds NB*32 activation rows and 256 weight rows of 128 B; as many stages as fit
+// in 160 KB of LDS are used as a ring: short tiles (ragged tails, and the
+// 128..160-row tiles chosen for weight-bound shapes) get three or four stages,
+// i.e. two or three K steps of loads in flight, which is what hides HBM latency
+// when the weights are streamed once.
+template <int NB> struct Ring {
+  static constexpr int kARows = NB * 32;
+  static constexpr int kStageSlots = (kARows + 256) * 8;          // 16-byte pieces
+  static constexpr int kFit = (160 * 1024) / (kStageSlots * 16);
+  static constexpr int kStages = kFit > 4 ? 4 : (NB == 2 ? 3 : kFit);   // NB==2 would fill all 160 KB
+};
+
+template <bool DUAL, int NB, int WM>
 __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
                                             const uint16_t* __restrict__ Be0,
                                             const uint16_t* __restrict__ Be1,
                                             uint16_t* __restrict__ C, int N, int K, int row0,
                                             int row1, int n0, uint4* smem, int wave) {
-  constexpr int SLOTS = 256 * 8;
-  uint4* As = smem;                      // [2][SLOTS]
-  uint4* Bs = smem + 2 * SLOTS;          // [2][SLOTS]
+  constexpr int NBW = NB - WM * 4 < 0 ? 0 : (NB - WM * 4 > 4 ? 4 : NB - WM * 4);
+  constexpr int S = Ring<NB>::kStages;
+  constexpr int SS = Ring<NB>::kStageSlots;
+  constexpr int AS = Ring<NB>::kARows * 8;           // slots of the A part of a stage
   const int lane = threadIdx.x & 63;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wn = wave & 3;
   const int ksteps = K / BK;
-  const int h = row1 - row0;
 
   // loads: a wavefront instruction fills 64 slots = 8 rows of 128 B.  Row group
   // rg = q*8 + wave.  Lane l -> row l/8, slot l%8 of the swizzled row, i.e. the
   // global piece (l%8) ^ ((row>>1)&7) with row>>1 = rg*4 + (l>>4).
+  // A row groups exist for rg < NB*4: q < NB/2 for every wavefront, plus
+  // q = NB/2 for wavefronts 0..3 when NB is odd.
+  constexpr int NAQ = NB / 2;
+  constexpr bool ODD = (NB & 1) != 0;
   const int lrow = lane >> 3;
-  const uint16_t* asrc[4];
+  const uint16_t* asrc[NAQ + 1];
   const uint16_t* bsrc[4];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < NAQ + 1; ++q) {
     const int rg = q * 8 + wave;
     const int piece = (lane & 7) ^ ((rg * 4 + (lane >> 4)) & 7);
     int r = row0 + rg * 8 + lrow;
     r = r < row1 ? r : row1 - 1;
     asrc[q] = A + size_t(r) * K + piece * 8;
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int rg = q * 8 + wave;
+    const int piece = (lane & 7) ^ ((rg * 4 + (lane >> 4)) & 7);
     const int br = rg * 8 + lrow;
     const uint16_t* base = (DUAL && br >= 128) ? Be1 : Be0;
     int n = n0 + ((DUAL && br >= 128) ? br - 128 : br);
     n = n < N ? n : N - 1;
     bsrc[q] = base + size_t(n) * K + piece * 8;
   }
-  auto issue = [&](int ks, int buf) {
+  const bool extra = ODD && wave < 4;                // this wavefront loads one more A row group
+  auto issue = [&](int ks) {
     const int kcol = ks * BK;
+    uint4* st = smem + (ks % S) * SS;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-      if ((q * 8 + wave) * 8 < h)        // skip row groups past the tile's last row
-        __builtin_amdgcn_global_load_lds((gptr_t)(asrc[q] + kcol),
-                                         (lptr_t)(As + buf * SLOTS + (q * 8 + wave) * 64), 16, 0, 0);
+    for (int q = 0; q < NAQ; ++q)
+      __builtin_amdgcn_global_load_lds((gptr_t)(asrc[q] + kcol), (lptr_t)(st + (q * 8 + wave) * 64),
+                                       16, 0, 0);
+    if (extra)
+      __builtin_amdgcn_global_load_lds((gptr_t)(asrc[NAQ] + kcol),
+                                       (lptr_t)(st + (NAQ * 8 + wave) * 64), 16, 0, 0);
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[q] + kcol),
-                                       (lptr_t)(Bs + buf * SLOTS + (q * 8 + wave) * 64), 16, 0, 0);
+                                       (lptr_t)(st + AS + (q * 8 + wave) * 64), 16, 0, 0);
+  };
+  // wait until at most `steps` younger steps of this wavefront's loads are in flight
+  auto wait_steps = [&](int steps) {
+    if (S >= 4 && steps >= 2) {
+      if (extra) wait_vmcnt<2 * (NAQ + 5)>(); else wait_vmcnt<2 * (NAQ + 4)>();
+    } else if (S >= 3 && steps >= 1) {
+      if (extra) wait_vmcnt<NAQ + 5>(); else wait_vmcnt<NAQ + 4>();
+    } else {
+      wait_vmcnt<0>();
+    }
   };
 
   constexpr int NA = NBW > 0 ? NBW : 1;
@@ -372,19 +409,24 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  const int arow = wm * 128;
+  const int arow = WM * 128;
   const int brow0 = DUAL ? wn * 32 : wn * 64;
   const int brow1 = DUAL ? 128 + wn * 32 : wn * 64 + 32;
 
-  issue(0, 0);
-  wait_vmcnt<0>();
-  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < S - 1; ++p)
+    if (p < ksteps) issue(p);
   for (int ks = 0; ks < ksteps; ++ks) {
-    const int buf = ks & 1;
-    if (ks + 1 < ksteps) issue(ks + 1, buf ^ 1);
+    // step ks must have landed; steps ks+1 .. ks+S-2 may still be in flight
+    const int younger = ksteps - 1 - ks;
+    wait_steps(younger < S - 2 ? younger : S - 2);
+    // a bare barrier (no fence): __syncthreads() would also drain the younger loads
+    asm volatile("s_barrier" ::: "memory");
+    // every wavefront has finished step ks-1, so its stage can take step ks+S-1
+    if (ks + S - 1 < ksteps) issue(ks + S - 1);
     if constexpr (NBW > 0) {
-      const uint4* Ab = As + buf * SLOTS;
-      const uint4* Bb = Bs + buf * SLOTS;
+      const uint4* Ab = smem + (ks % S) * SS;
+      const uint4* Bb = Ab + AS;
       uint4 fa[2][NA], fb[2][2];
       auto read_frags = [&](int kk, int set) {
         const int piece = kk * 2 + (lane >> 5);
@@ -418,8 +460,6 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    wait_vmcnt<0>();                     // the next step's tiles have landed
-    __syncthreads();
   }
 
   if constexpr (NBW > 0) {
@@ -442,6 +482,14 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
       }
     }
   }
+}
+
+template <bool DUAL, int NB>
+__device__ __forceinline__ void gemm8w_tile(const uint16_t* A, const uint16_t* Be0,
+                                            const uint16_t* Be1, uint16_t* C, int N, int K,
+                                            int row0, int row1, int n0, uint4* smem, int wave) {
+  if (wave < 4) gemm8w_body<DUAL, NB, 0>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave);
+  else gemm8w_body<DUAL, NB, 1>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave);
 }
 
 template <bool DUAL>
@@ -472,15 +520,15 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
   const uint16_t* Be0 = B0 + size_t(e) * N * K;
   const uint16_t* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nb = (row1 - row0 + 31) >> 5;             // valid 32-row blocks of the tile
-  int nbw = nb - (wave >> 2) * 4;                     // ... of this wavefront's half
-  nbw = nbw < 0 ? 0 : (nbw > 4 ? 4 : nbw);
-  switch (nbw) {
-    case 0: gemm8w_body<DUAL, 0>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 1: gemm8w_body<DUAL, 1>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 2: gemm8w_body<DUAL, 2>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 3: gemm8w_body<DUAL, 3>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    default: gemm8w_body<DUAL, 4>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+  switch ((row1 - row0 + 31) >> 5) {     // valid 32-row blocks of the tile
+    case 1: gemm8w_tile<DUAL, 1>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 2: gemm8w_tile<DUAL, 2>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 3: gemm8w_tile<DUAL, 3>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 4: gemm8w_tile<DUAL, 4>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 5: gemm8w_tile<DUAL, 5>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 6: gemm8w_tile<DUAL, 6>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    case 7: gemm8w_tile<DUAL, 7>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+    default: gemm8w_tile<DUAL, 8>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
   }
 }
 
@@ -583,11 +631,14 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
                     int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
                     void* ys, const FfnWs& ws, hipStream_t s) {
   const int H = c.hidden, I = c.inter_local;
-  const int max_mt = rows_capacity / 256 + n_experts;
-  MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, 256,
+  // Few rows per expert means the weights are streamed about once: cap the tile
+  // height at 160 rows there, which leaves room for a three-stage ring.
+  const int bm = rows_capacity / n_experts <= 320 ? 160 : 256;
+  const int max_mt = rows_capacity / bm + n_experts;
+  MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, bm,
              rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 1);
   const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
-  constexpr int lds = 4 * 256 * 8 * 16;   // A and B, double buffered: 128 KB
+  constexpr int lds = 160 * 1024 - 4096;  // the ring of every tile height fits below this
   const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt * nt2 + 7) / 8 * 8;
   auto k1 = ffn_gemm8w_kernel<true>;
   auto k2 = ffn_gemm8w_kernel<false>;
