@@ -12,6 +12,17 @@ namespace moe {
 
 namespace {
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// streaming (non-temporal) 16-byte accesses: data that is touched once
+__device__ __forceinline__ uint4 nt_load16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(static_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store16(void* p, uint4 v) {
+  u32x4_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, static_cast<u32x4_t*>(p));
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
@@ -40,24 +51,49 @@ __global__ __launch_bounds__(256) void combine_bf16_kernel(
     wt = w[size_t(t) * k + lane];
   }
   const uint64_t have = __ballot(pos >= 0);
-  for (int c = lane; c < row8; c += 64) {
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  constexpr int P = 4;                          // pieces per lane in flight
+  for (int c0 = lane; c0 < row8; c0 += 64 * P) {
+    float acc[P][8];
+#pragma unroll
+    for (int i = 0; i < P; ++i)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc[i][q] = 0.f;
     uint64_t m = have;
     while (m) {                               // ascending j
       const int j = __ffsll((unsigned long long)m) - 1;
       m &= m - 1;
       const int p = __shfl(pos, j);
       const float wj = __shfl(wt, j);
-      const uint4 v = ys[size_t(p) * row8 + c];
-      fma8(acc, wj, v);
+      const uint4* row = ys + size_t(p) * row8;
+      uint4 v[P];
+#pragma unroll
+      for (int i = 0; i < P; ++i)
+        if (c0 + 64 * i < row8) v[i] = nt_load16(row + c0 + 64 * i);
+#pragma unroll
+      for (int i = 0; i < P; ++i)
+        if (c0 + 64 * i < row8) fma8(acc[i], wj, v[i]);
     }
     if (shared_ys) {
-      const uint4 v = shared_ys[size_t(t) * row8 + c];
-      fma8(acc, 1.0f, v);
+      const uint4* row = shared_ys + size_t(t) * row8;
+      uint4 v[P];
+#pragma unroll
+      for (int i = 0; i < P; ++i)
+        if (c0 + 64 * i < row8) v[i] = nt_load16(row + c0 + 64 * i);
+#pragma unroll
+      for (int i = 0; i < P; ++i)
+        if (c0 + 64 * i < row8) fma8(acc[i], 1.0f, v[i]);
     }
-    float4* o = out + (size_t(t) * row8 + c) * 2;
-    o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+      const int c = c0 + 64 * i;
+      if (c < row8) {
+        float4* o = out + (size_t(t) * row8 + c) * 2;
+        nt_store16(o, make_uint4(__float_as_uint(acc[i][0]), __float_as_uint(acc[i][1]),
+                                 __float_as_uint(acc[i][2]), __float_as_uint(acc[i][3])));
+        nt_store16(o + 1, make_uint4(__float_as_uint(acc[i][4]), __float_as_uint(acc[i][5]),
+                                     __float_as_uint(acc[i][6]), __float_as_uint(acc[i][7])));
+      }
+    }
   }
 }
 

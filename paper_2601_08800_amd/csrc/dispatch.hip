@@ -16,6 +16,17 @@ namespace moe {
 
 namespace {
 
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+// streaming (non-temporal) 16-byte accesses: data that is touched once
+__device__ __forceinline__ uint4 nt_load16(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(static_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store16(void* p, uint4 v) {
+  u32x4_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, static_cast<u32x4_t*>(p));
+}
+
 constexpr int kSub = 64;   // assignments per histogram column: one wavefront
 
 __device__ __forceinline__ uint64_t lanemask_lt() {
@@ -139,7 +150,7 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __res
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
       const int c = c0 + i * 64 + lane;
-      if (c < row16) v[i] = src[c];
+      if (c < row16) v[i] = nt_load16(src + c);
     }
     uint64_t m = have;
     while (m) {
@@ -150,7 +161,7 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __res
 #pragma unroll
       for (int i = 0; i < PIECES; ++i) {
         const int c = c0 + i * 64 + lane;
-        if (c < row16) dst[c] = v[i];
+        if (c < row16) nt_store16(dst + c, v[i]);
       }
     }
   }

@@ -685,17 +685,18 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
   const int avg = rows_capacity / n_experts;
   const bool fp8 = c.weight_dtype == MOE_FP8_E4M3_B128;
 #define MOE_FFN_ARGS c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, s_gate, s_up, s_down, ys, ws, s
-  if (avg <= 32) {
-    if (fp8) launch_mfma_pair<32, 128, 32, 32, 256, 64, true>(MOE_FFN_ARGS);
-    else launch_mfma_pair<32, 128, 32, 32, 256, 64, false>(MOE_FFN_ARGS);
+  if (fp8) {
+    // weight streaming: the 32-row variant keeps four workgroups per CU in
+    // flight, which is what hides the HBM latency of its register-staged loads
+    launch_mfma_pair<32, 128, 32, 32, 256, 64, true>(MOE_FFN_ARGS);
+  } else if (avg <= 32) {
+    launch_mfma_pair<32, 128, 32, 32, 256, 64, false>(MOE_FFN_ARGS);
   } else if (avg <= 64) {
-    if (fp8) launch_mfma_pair<64, 128, 64, 32, 256, 64, true>(MOE_FFN_ARGS);
-    else launch_mfma_pair<64, 128, 64, 32, 256, 64, false>(MOE_FFN_ARGS);
-  } else if (!fp8 && H % BK == 0 && I % BK == 0) {
+    launch_mfma_pair<64, 128, 64, 32, 256, 64, false>(MOE_FFN_ARGS);
+  } else if (H % BK == 0 && I % BK == 0) {
     launch_mfma256(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
   } else {
-    if (fp8) launch_mfma_pair<128, 64, 64, 32, 128, 64, true>(MOE_FFN_ARGS);
-    else launch_mfma_pair<128, 64, 64, 32, 128, 64, false>(MOE_FFN_ARGS);
+    launch_mfma_pair<128, 64, 64, 32, 128, 64, false>(MOE_FFN_ARGS);
   }
 #undef MOE_FFN_ARGS
   return hipGetLastError();

@@ -126,21 +126,26 @@ __global__ __launch_bounds__(256) void gate_wnorm_kernel(const void* __restrict_
   if (lane == 0) wnorm2[e] = (float)(s * (1.0 + 1e-6));
 }
 
-// ------------------------------------- stage 1 (fp32 inputs): fp64 VALU gate
-// One workgroup per token; each wavefront takes every 4th expert.
-__global__ __launch_bounds__(256) void gate_f64_kernel(const float* __restrict__ x,
-                                                      const float* __restrict__ gate_w, int T,
+// ----------------------- stage 1 (fp32 inputs, or few tokens): fp64 VALU gate
+// One workgroup per token; each wavefront takes every 4th expert.  Exact
+// products, fp64 sums: the logits are good to the fp32 store.  Used for fp32
+// activations and for decode-sized batches, where a tiled GEMM would leave the
+// chip idle and the fp64 work is negligible.
+template <bool BF16>
+__global__ __launch_bounds__(256) void gate_f64_kernel(const void* __restrict__ x,
+                                                      const void* __restrict__ gate_w, int T,
                                                       int H, int E, float* __restrict__ logits,
                                                       float* __restrict__ xnorm2) {
   const int t = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const float* xr = x + size_t(t) * H;
+  const size_t eb = BF16 ? 2 : 4;
+  const char* xr = static_cast<const char*>(x) + size_t(t) * H * eb;
   for (int e = wave; e < E; e += 4) {
-    const double z = wave_dot64<false>(xr, gate_w + size_t(e) * H, H, lane);
+    const double z = wave_dot64<BF16>(xr, static_cast<const char*>(gate_w) + size_t(e) * H * eb, H, lane);
     if (lane == 0) logits[size_t(t) * E + e] = (float)z;
   }
   if (wave == 0) {
-    const double s = wave_dot64<false>(xr, xr, H, lane);
+    const double s = wave_dot64<BF16>(xr, xr, H, lane);
     if (lane == 0) xnorm2[t] = (float)(s * (1.0 + 1e-6));
   }
 }
@@ -699,16 +704,23 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   if (!logits_in) {
     logits = ws.logits;
     sc.have_norms = 1;
-    if (bf16) {
+    // decode-sized batches: the fp64 gate costs T*E*H fused multiply-adds, a few
+    // microseconds up to about 2^28 of them, and needs (almost) no re-scoring
+    const bool small = size_t(T) * E * H <= (size_t(1) << 28);
+    if (bf16 && !small) {
       const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN);
       MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(256), 0, s,
-                         static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T,
-                         H, E, ws.logits, ws.xnorm2);
+                 static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
+                 ws.logits, ws.xnorm2);
       // chains of kGateChainSteps*64 products; +2 for the flush and the store
       sc.chain_err = (2.f * kGateChainSteps * GBK + 2.f) * kUlp;
     } else {
-      MOE_LAUNCH(MOE_K_GATE_GEMM, gate_f64_kernel, dim3(T), dim3(256), 0, s, static_cast<const float*>(x),
-                         static_cast<const float*>(gate_w), T, H, E, ws.logits, ws.xnorm2);
+      if (bf16)
+        MOE_LAUNCH(MOE_K_GATE_GEMM, gate_f64_kernel<true>, dim3(T), dim3(256), 0, s, x, gate_w, T,
+                   H, E, ws.logits, ws.xnorm2);
+      else
+        MOE_LAUNCH(MOE_K_GATE_GEMM, gate_f64_kernel<false>, dim3(T), dim3(256), 0, s, x, gate_w, T,
+                   H, E, ws.logits, ws.xnorm2);
       // fp64 sums: the only error is the fp32 store, covered by the 2 ulp term
       sc.chain_err = 1e-12f;
     }
