@@ -421,7 +421,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     const int younger = ksteps - 1 - ks;
     wait_steps(younger < S - 2 ? younger : S - 2);
     // a bare barrier (no fence): __syncthreads() would also drain the younger loads
-    asm volatile("s_barrier" ::: "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     // every wavefront has finished step ks-1, so its stage can take step ks+S-1
     if (ks + S - 1 < ksteps) issue(ks + S - 1);
     if constexpr (NBW > 0) {

@@ -30,30 +30,53 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr float kUlp = 5.9604645e-8f;   // 2^-24
 
 // ------------------------------------------------------------------ helpers
+// Pairwise lane exchange, step s pairs disjoint groups of 2^s lanes: steps 0..3
+// are DPP moves inside a row of 16 lanes (quad permutes, then the half-row and
+// row mirrors: after the quads are uniform a mirror pairs each lane with a lane
+// of the other group), steps 4 and 5 cross rows through the LDS crossbar.
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+
+template <int STEP>
+__device__ __forceinline__ int lane_xchg32(int v) {
+  if (STEP == 0) return dpp_mov<0xB1>(v);        // quad_perm [1,0,3,2]
+  if (STEP == 1) return dpp_mov<0x4E>(v);        // quad_perm [2,3,0,1]
+  if (STEP == 2) return dpp_mov<0x141>(v);       // row_half_mirror
+  if (STEP == 3) return dpp_mov<0x140>(v);       // row_mirror
+  return __shfl_xor(v, STEP == 4 ? 16 : 32);
+}
+
+template <int STEP>
+__device__ __forceinline__ int lane_xchg(int v) { return lane_xchg32<STEP>(v); }
+template <int STEP>
+__device__ __forceinline__ float lane_xchg(float v) {
+  return __builtin_bit_cast(float, lane_xchg32<STEP>(__builtin_bit_cast(int, v)));
+}
+template <int STEP>
+__device__ __forceinline__ double lane_xchg(double v) {
+  const uint64_t u = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)lane_xchg32<STEP>((int)(uint32_t)u);
+  const uint32_t hi = (uint32_t)lane_xchg32<STEP>((int)(uint32_t)(u >> 32));
+  return __builtin_bit_cast(double, (uint64_t(hi) << 32) | lo);
+}
+
+#define MOE_ALL_STEPS(F) F(0) F(1) F(2) F(3) F(4) F(5)
+
 template <typename T>
 __device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+#define STEP_(S) v += lane_xchg<S>(v);
+  MOE_ALL_STEPS(STEP_)
+#undef STEP_
   return v;
 }
 
 template <typename T>
 __device__ __forceinline__ T wave_max(T v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    T o = __shfl_xor(v, off);
-    v = o > v ? o : v;
-  }
-  return v;
-}
-
-template <typename T>
-__device__ __forceinline__ T wave_min(T v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    T o = __shfl_xor(v, off);
-    v = o < v ? o : v;
-  }
+#define STEP_(S) { const T o = lane_xchg<S>(v); v = o > v ? o : v; }
+  MOE_ALL_STEPS(STEP_)
+#undef STEP_
   return v;
 }
 
@@ -61,17 +84,35 @@ __device__ __forceinline__ T wave_min(T v) {
 // "no candidate".  Result is the same in every lane.
 template <typename T>
 __device__ __forceinline__ void wave_argmax(T& v, int& idx) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    T ov = __shfl_xor(v, off);
-    int oi = __shfl_xor(idx, off);
-    bool take = (oi != INT_MAX) && (idx == INT_MAX || ov > v || (ov == v && oi < idx));
-    if (take) { v = ov; idx = oi; }
+#define STEP_(S)                                                                          \
+  {                                                                                       \
+    const T ov = lane_xchg<S>(v);                                                         \
+    const int oi = lane_xchg<S>(idx);                                                     \
+    const bool take = (oi != INT_MAX) && (idx == INT_MAX || ov > v || (ov == v && oi < idx)); \
+    if (take) { v = ov; idx = oi; }                                                       \
   }
+  MOE_ALL_STEPS(STEP_)
+#undef STEP_
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) {
   return __uint_as_float(hi16 << 16);
+}
+
+// fp64 dot product of two 16-byte pieces (8 bf16 or 4 fp32), added to acc.
+template <bool BF16>
+__device__ __forceinline__ double piece_dot64(const uint4& a, const uint4& b, double acc) {
+  const uint32_t av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (BF16) {
+      acc = fma((double)bf16_bits_to_f32(av[i] & 0xffffu), (double)bf16_bits_to_f32(bv[i] & 0xffffu), acc);
+      acc = fma((double)bf16_bits_to_f32(av[i] >> 16), (double)bf16_bits_to_f32(bv[i] >> 16), acc);
+    } else {
+      acc = fma((double)__uint_as_float(av[i]), (double)__uint_as_float(bv[i]), acc);
+    }
+  }
+  return acc;
 }
 
 // fp64 dot product of one token row with one gate row, one wavefront, fixed
@@ -153,11 +194,13 @@ __global__ __launch_bounds__(256) void gate_f64_kernel(const void* __restrict__ 
 // ------------------------------------------ stage 1 (bf16): MFMA gate GEMM
 // Block tile 64 tokens x 128 experts, K step 64, 4 wavefronts as 2 (M) x 2 (N),
 // each 32 x 64 = two 32x32 MFMA tiles.  LDS tiles are [row][8 pieces of 16 B]
-// with the piece index XOR-ed by (row & 7) so that the 16-byte operand reads of
-// 8 consecutive rows fall in different banks.
+// with the piece index XOR-ed by (row/2)&7 so that the 16 lanes the LDS serves
+// per cycle fall on 16 different 16-byte columns.
 constexpr int GBM = 64, GBN = 128, GBK = 64;
 
-__device__ __forceinline__ int swz(int row, int piece) { return row * 8 + (piece ^ (row & 7)); }
+__device__ __forceinline__ int swz(int row, int piece) {
+  return row * 8 + (piece ^ ((row >> 1) & 7));
+}
 
 template <int CHAIN_STEPS>
 __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restrict__ x,
@@ -348,17 +391,20 @@ __device__ __forceinline__ void group_stage(const SelCfg& c, const Keys<FT, EPL>
       if (i * 64 >= c.E) break;
       FT m1 = K.key[i], m2 = -INFINITY, me = K.eps[i];
       FT l1 = K.key[i] - K.eps[i], l2 = -INFINITY;      // two largest lower bounds
-      for (int off = 1; off < gs; off <<= 1) {
-        const FT o1 = __shfl_xor(m1, off), o2 = __shfl_xor(m2, off), oe = __shfl_xor(me, off);
-        const FT p1 = __shfl_xor(l1, off), p2 = __shfl_xor(l2, off);
-        const FT lo = m1 < o1 ? m1 : o1, hi2 = m2 > o2 ? m2 : o2;
-        m1 = m1 > o1 ? m1 : o1;
-        m2 = lo > hi2 ? lo : hi2;
-        me = me > oe ? me : oe;
-        const FT ql = l1 < p1 ? l1 : p1, qh = l2 > p2 ? l2 : p2;
-        l1 = l1 > p1 ? l1 : p1;
-        l2 = ql > qh ? ql : qh;
-      }
+#define STEP_(S)                                                                   \
+  if ((1 << S) < gs) {                                                             \
+    const FT o1 = lane_xchg<S>(m1), o2 = lane_xchg<S>(m2), oe = lane_xchg<S>(me);  \
+    const FT p1 = lane_xchg<S>(l1), p2 = lane_xchg<S>(l2);                         \
+    const FT lo = m1 < o1 ? m1 : o1, hi2 = m2 > o2 ? m2 : o2;                      \
+    m1 = m1 > o1 ? m1 : o1;                                                        \
+    m2 = lo > hi2 ? lo : hi2;                                                      \
+    me = me > oe ? me : oe;                                                        \
+    const FT ql = l1 < p1 ? l1 : p1, qh = l2 > p2 ? l2 : p2;                       \
+    l1 = l1 > p1 ? l1 : p1;                                                        \
+    l2 = ql > qh ? ql : qh;                                                        \
+  }
+      MOE_ALL_STEPS(STEP_)
+#undef STEP_
       const FT sum = c.gn == 2 ? m1 + m2 : m1;
       const FT nth_low = c.gn == 2 ? l2 : l1;            // <= the gn-th largest exact key
       if (K.key[i] + K.eps[i] >= nth_low) need |= 1u << i;
@@ -553,23 +599,61 @@ __global__ __launch_bounds__(256) void route_recheck_kernel(
   __shared__ int xlist[512];
   __shared__ double zx[512];
   __shared__ int n_x;
+  __shared__ double part[4][8];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n_list = counters[0];
   const size_t eb = BF16 ? 2 : 4;
 
   // exact logits of the experts in xlist[0..n) -> zx[e]; all four wavefronts
+  // The whole workgroup works on every dot product (thread-strided 16-byte
+  // pieces, the token row is loaded once per batch of CB experts), so many loads
+  // are in flight; partial sums are combined in a fixed order.
+  constexpr int CB = 8;
   auto exact_logits = [&](int t, int n) {
-    for (int q = wave; q < n; q += 4) {
-      const int e = xlist[q];
-      double z;
-      if (logits_in) {
-        z = (double)logits_in[size_t(t) * c.E + e];
-      } else {
-        z = wave_dot64<BF16>(static_cast<const char*>(x) + size_t(t) * H * eb,
-                             static_cast<const char*>(gate_w) + size_t(e) * H * eb, H, lane);
+    if (logits_in) {
+      for (int q = threadIdx.x; q < n; q += 256) {
+        const int e = xlist[q];
+        double z = (double)logits_in[size_t(t) * c.E + e];
+        if (logit_bias) z += (double)logit_bias[e];
+        zx[e] = z;
       }
-      if (logit_bias) z += (double)logit_bias[e];
-      if (lane == 0) zx[e] = z;
+      return;
+    }
+    const char* xrow = static_cast<const char*>(x) + size_t(t) * H * eb;
+    const int n16 = int(H * eb / 16);
+    for (int q0 = 0; q0 < n; q0 += CB) {
+      double acc[CB];
+      const char* wrow[CB];
+#pragma unroll
+      for (int i = 0; i < CB; ++i) {
+        acc[i] = 0.0;
+        const int e = xlist[q0 + i < n ? q0 + i : n - 1];
+        wrow[i] = static_cast<const char*>(gate_w) + size_t(e) * H * eb;
+      }
+      for (int p = threadIdx.x; p < n16; p += 256) {
+        const uint4 a = *reinterpret_cast<const uint4*>(xrow + size_t(p) * 16);
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+          if (q0 + i < n) {
+            const uint4 b = *reinterpret_cast<const uint4*>(wrow[i] + size_t(p) * 16);
+            acc[i] = piece_dot64<BF16>(a, b, acc[i]);
+          }
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < CB; ++i) {
+        const double sm = wave_sum(acc[i]);
+        if (lane == 0) part[wave][i] = sm;
+      }
+      __syncthreads();
+      if (threadIdx.x < CB && q0 + int(threadIdx.x) < n) {
+        const int e = xlist[q0 + threadIdx.x];
+        double z = ((part[0][threadIdx.x] + part[1][threadIdx.x]) + part[2][threadIdx.x]) +
+                   part[3][threadIdx.x];
+        if (logit_bias) z += (double)logit_bias[e];
+        zx[e] = z;
+      }
+      __syncthreads();
     }
   };
   // wavefront 0: list the experts flagged in `want` that are not yet exact
