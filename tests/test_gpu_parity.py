@@ -29,6 +29,18 @@ SMALL = {
     "fp8_decode_small": gen.CONFIGS["c5"].replace(name="fp8_decode_small", T=40, H=256, E=16, k=4,
                                                   I=256, expert_lo=0, expert_hi=16, zipf_s=None,
                                                   n_groups=1, topk_groups=1, group_score_n=0),
+    # sizes that are not multiples of the tile shapes: K and N tails, odd E and k
+    "ragged_dims": gen.CONFIGS["c2p"].replace(name="ragged_dims", T=333, H=328, E=20, k=3, I=200),
+    "ragged_dims_decode": gen.CONFIGS["c2d"].replace(name="ragged_dims_decode", T=9, H=136, E=12,
+                                                     k=5, I=72),
+    # prefill-size groups whose K is not a multiple of 64 (generic 128-row kernel)
+    "ragged_dims_prefill": gen.CONFIGS["c2p"].replace(name="ragged_dims_prefill", T=900, H=328, E=4,
+                                                      k=2, I=200),
+    # prefill-size groups on the 256-row kernel with N tails (I = 128+64, H = 256+64)
+    "tail_256": gen.CONFIGS["c2p"].replace(name="tail_256", T=900, H=320, E=4, k=2, I=192),
+    # many experts per lane slot and a large k
+    "wide_gate": gen.CONFIGS["c2p"].replace(name="wide_gate", T=150, H=256, E=512, k=16, I=64,
+                                            expert_lo=100, expert_hi=400),
     # fp8 weights, natural routing
     "fp8_small": gen.CONFIGS["c5"].replace(name="fp8_small", T=300, H=512, E=64, k=8, I=512,
                                            expert_lo=0, expert_hi=8, zipf_s=None),
