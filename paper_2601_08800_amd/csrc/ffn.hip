@@ -507,12 +507,18 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
   if ((pid >> 3) >= per_xcd || logical >= total) return;
   int mtile = logical / n_ntiles, ntile = logical - mtile * n_ntiles;
   if (m_fastest) {
-    // inside an expert's block of tiles walk the M tiles first, so that the
-    // workgroups that share a weight panel are neighbours
+    // Inside an expert's block of tiles: groups of up to four M tiles; per group
+    // all N tiles, M tile fastest.  The ~32 workgroups an XCD runs at a time then
+    // form a (4 M tiles) x (8 N tiles) patch: every weight panel is shared by
+    // four of them, every activation panel by eight.
     const int first = tiles[4 + kTileRec * mtile], cnt = tiles[5 + kTileRec * mtile];
     const int local = logical - first * n_ntiles;
-    ntile = local / cnt;
-    mtile = first + (local - ntile * cnt);
+    const int gsz = 4 * n_ntiles;
+    const int grp = local / gsz, rem = local - grp * gsz;
+    const int left = cnt - grp * 4;
+    const int mc = left < 4 ? left : 4;
+    ntile = rem / mc;
+    mtile = first + grp * 4 + (rem - ntile * mc);
   }
   const int e = tiles[1 + kTileRec * mtile], row0 = tiles[2 + kTileRec * mtile],
             row1 = tiles[3 + kTileRec * mtile];

@@ -18,7 +18,7 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // route
 constexpr int kRouteCounterBytes = 256;       // [0]=tokens re-scored in fp64
-constexpr int kGateChainSteps = 2;            // K-steps of 64 per fp32 accumulation chain
+constexpr int kGateChainSteps = 1;            // K-steps of 64 per fp32 accumulation chain
 struct RouteWs {
   int32_t* counters;   // [64]
   float* logits;       // [T,E] fast logits (fp32)
