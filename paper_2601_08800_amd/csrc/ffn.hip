@@ -324,11 +324,17 @@ __device__ __forceinline__ int swz2(int row, int piece) {
 // 128..160-row tiles chosen for weight-bound shapes) get three or four stages,
 // i.e. two or three K steps of loads in flight, which is what hides HBM latency
 // when the weights are streamed once.
+// K step per stage: 64, i.e. 128-byte LDS rows, so that every load instruction
+// moves whole cache lines.  (A K step of 32 would allow four stages for the tall
+// tiles too, but its 64-byte row pieces halve the efficiency of the load path:
+// measured 8 % slower on the 256-row tiles.)
 template <int NB> struct Ring {
+  static constexpr int kBK = 64;
+  static constexpr int kPPR = kBK / 8;                              // 16-byte pieces per row
   static constexpr int kARows = NB * 32;
-  static constexpr int kStageSlots = (kARows + 256) * 8;          // 16-byte pieces
-  static constexpr int kFit = (160 * 1024) / (kStageSlots * 16);
-  static constexpr int kStages = kFit > 4 ? 4 : (NB == 2 ? 3 : kFit);   // NB==2 would fill all 160 KB
+  static constexpr int kStageSlots = (kARows + 256) * kPPR;
+  static constexpr int kFit = (160 * 1024 - 4096) / (kStageSlots * 16);
+  static constexpr int kStages = kFit > 4 ? 4 : kFit;
 };
 
 template <bool DUAL, int NB, int WM>
@@ -340,42 +346,52 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   constexpr int NBW = NB - WM * 4 < 0 ? 0 : (NB - WM * 4 > 4 ? 4 : NB - WM * 4);
   constexpr int S = Ring<NB>::kStages;
   constexpr int SS = Ring<NB>::kStageSlots;
-  constexpr int AS = Ring<NB>::kARows * 8;           // slots of the A part of a stage
+  constexpr int KS = Ring<NB>::kBK;                  // K step
+  constexpr int PPR = Ring<NB>::kPPR;                // pieces per LDS row: 8 or 4
+  constexpr int RPI = 64 / PPR;                      // rows filled by one load instruction
+  constexpr int AS = Ring<NB>::kARows * PPR;         // slots of the A part of a stage
   const int lane = threadIdx.x & 63;
   const int wn = wave & 3;
-  const int ksteps = K / BK;
+  const int ksteps = K / KS;
 
-  // loads: a wavefront instruction fills 64 slots = 8 rows of 128 B.  Row group
-  // rg = q*8 + wave.  Lane l -> row l/8, slot l%8 of the swizzled row, i.e. the
-  // global piece (l%8) ^ ((row>>1)&7) with row>>1 = rg*4 + (l>>4).
-  // A row groups exist for rg < NB*4: q < NB/2 for every wavefront, plus
-  // q = NB/2 for wavefronts 0..3 when NB is odd.
-  constexpr int NAQ = NB / 2;
-  constexpr bool ODD = (NB & 1) != 0;
-  const int lrow = lane >> 3;
+  // LDS row r keeps its piece p at slot p ^ f(r): f = (r/2)&7 for 128-byte rows,
+  // (r/4)&3 for 64-byte rows; both keep the 16 lanes the LDS serves per cycle
+  // on 16 different 16-byte columns.
+  auto slot = [&](int row, int piece) {
+    return row * PPR + (piece ^ (PPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3));
+  };
+  // loads: a wavefront instruction fills 64 consecutive slots = RPI rows.  Row
+  // group rg = q*8 + wave; lane l -> row l/PPR, and it fetches the piece that
+  // belongs in slot l%PPR of that row: (l%PPR) ^ ((rg*4 + l/16) & (PPR-1)).
+  // A row groups exist for rg < NB*32/RPI.
+  constexpr int AGROUPS = NB * 32 / RPI;
+  constexpr int NAQ = AGROUPS / 8;                   // full rounds of 8 wavefronts
+  constexpr int AREM = AGROUPS % 8;                  // wavefronts 0..AREM-1 load one more
+  constexpr int NBQ = 256 / RPI / 8;                 // weight row groups per wavefront
+  const int lrow = lane / PPR;
   const uint16_t* asrc[NAQ + 1];
-  const uint16_t* bsrc[4];
+  const uint16_t* bsrc[NBQ];
 #pragma unroll
   for (int q = 0; q < NAQ + 1; ++q) {
     const int rg = q * 8 + wave;
-    const int piece = (lane & 7) ^ ((rg * 4 + (lane >> 4)) & 7);
-    int r = row0 + rg * 8 + lrow;
+    const int piece = (lane % PPR) ^ ((rg * 4 + (lane >> 4)) & (PPR - 1));
+    int r = row0 + rg * RPI + lrow;
     r = r < row1 ? r : row1 - 1;
     asrc[q] = A + size_t(r) * K + piece * 8;
   }
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < NBQ; ++q) {
     const int rg = q * 8 + wave;
-    const int piece = (lane & 7) ^ ((rg * 4 + (lane >> 4)) & 7);
-    const int br = rg * 8 + lrow;
+    const int piece = (lane % PPR) ^ ((rg * 4 + (lane >> 4)) & (PPR - 1));
+    const int br = rg * RPI + lrow;
     const uint16_t* base = (DUAL && br >= 128) ? Be1 : Be0;
     int n = n0 + ((DUAL && br >= 128) ? br - 128 : br);
     n = n < N ? n : N - 1;
     bsrc[q] = base + size_t(n) * K + piece * 8;
   }
-  const bool extra = ODD && wave < 4;                // this wavefront loads one more A row group
+  const bool extra = AREM > 0 && wave < AREM;        // this wavefront loads one more A row group
   auto issue = [&](int ks) {
-    const int kcol = ks * BK;
+    const int kcol = ks * KS;
     uint4* st = smem + (ks % S) * SS;
 #pragma unroll
     for (int q = 0; q < NAQ; ++q)
@@ -385,16 +401,17 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
       __builtin_amdgcn_global_load_lds((gptr_t)(asrc[NAQ] + kcol),
                                        (lptr_t)(st + (NAQ * 8 + wave) * 64), 16, 0, 0);
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < NBQ; ++q)
       __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[q] + kcol),
                                        (lptr_t)(st + AS + (q * 8 + wave) * 64), 16, 0, 0);
   };
   // wait until at most `steps` younger steps of this wavefront's loads are in flight
+  constexpr int LPS = NAQ + NBQ;
   auto wait_steps = [&](int steps) {
     if (S >= 4 && steps >= 2) {
-      if (extra) wait_vmcnt<2 * (NAQ + 5)>(); else wait_vmcnt<2 * (NAQ + 4)>();
+      if (extra) wait_vmcnt<2 * (LPS + 1)>(); else wait_vmcnt<2 * LPS>();
     } else if (S >= 3 && steps >= 1) {
-      if (extra) wait_vmcnt<NAQ + 5>(); else wait_vmcnt<NAQ + 4>();
+      if (extra) wait_vmcnt<LPS + 1>(); else wait_vmcnt<LPS>();
     } else {
       wait_vmcnt<0>();
     }
@@ -412,6 +429,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   const int arow = WM * 128;
   const int brow0 = DUAL ? wn * 32 : wn * 64;
   const int brow1 = DUAL ? 128 + wn * 32 : wn * 64 + 32;
+  constexpr int NKK = KS / 16;                       // MFMA sub-steps per K step
 
 #pragma unroll
   for (int p = 0; p < S - 1; ++p)
@@ -430,17 +448,17 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
       uint4 fa[2][NA], fb[2][2];
       auto read_frags = [&](int kk, int set) {
         const int piece = kk * 2 + (lane >> 5);
-        fb[set][0] = Bb[swz2(brow0 + (lane & 31), piece)];
-        fb[set][1] = Bb[swz2(brow1 + (lane & 31), piece)];
+        fb[set][0] = Bb[slot(brow0 + (lane & 31), piece)];
+        fb[set][1] = Bb[slot(brow1 + (lane & 31), piece)];
 #pragma unroll
-        for (int i = 0; i < NBW; ++i) fa[set][i] = Ab[swz2(arow + i * 32 + (lane & 31), piece)];
+        for (int i = 0; i < NBW; ++i) fa[set][i] = Ab[slot(arow + i * 32 + (lane & 31), piece)];
       };
       read_frags(0, 0);
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
+      for (int kk = 0; kk < NKK; ++kk) {
         const int set = kk & 1;
         __builtin_amdgcn_sched_barrier(0);
-        if (kk < 3) read_frags(kk + 1, set ^ 1);
+        if (kk < NKK - 1) read_frags(kk + 1, set ^ 1);
         const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[set][0]);
         const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[set][1]);
 #pragma unroll
@@ -449,7 +467,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
           acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
           acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
         }
-        if (kk < 3 && NBW >= 2) {
+        if (kk < NKK - 1 && NBW >= 2) {
 #pragma unroll
           for (int i = 0; i < NBW + 2; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
