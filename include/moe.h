@@ -187,6 +187,12 @@ typedef enum {
  * recording; 0: stop recording and destroy the pool.  Not thread-safe. */
 moe_status moe_profile_enable(int32_t max_records);
 
+/* Restrict recording to the kernels whose bit (1 << moe_kernel_id) is set in
+ * `mask` (default: all).  Recording one kernel costs two event records per
+ * launch, so a benchmark can time its dominant kernel inside the timed region
+ * without slowing the region down by the other launches' events. */
+moe_status moe_profile_filter(uint32_t mask);
+
 /* Synchronises on the recorded events, then adds up, per moe_kernel_id, the
  * elapsed milliseconds and the number of recorded launches (host arrays of
  * MOE_K_COUNT entries), and clears the records (recording stays enabled). */

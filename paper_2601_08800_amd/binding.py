@@ -15,6 +15,7 @@ _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatch",
            "moe_expert_ffn", "moe_combine", "moe_profile_enable", "moe_profile_read",
+           "moe_profile_filter",
            "moe_kernel_name")
 MOE_K_COUNT = 12
 
@@ -71,6 +72,8 @@ def load_library():
         lib.moe_profile_enable.argtypes = [i32]
         lib.moe_profile_read.restype = ctypes.c_int
         lib.moe_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+        lib.moe_profile_filter.restype = ctypes.c_int
+        lib.moe_profile_filter.argtypes = [ctypes.c_uint32]
         lib.moe_kernel_name.restype = ctypes.c_char_p
         lib.moe_kernel_name.argtypes = [i32]
         _lib = lib
@@ -148,6 +151,18 @@ def moe_combine(cfg, T, ys, inv, topk_w, shared_ys, out, stream=None):
 
 def moe_profile_enable(max_records: int):
     _check(load_library().moe_profile_enable(max_records), "moe_profile_enable")
+
+
+def moe_profile_filter(names=None):
+    """Record only the named kernels (None: all)."""
+    lib = load_library()
+    mask = 0xffffffff
+    if names is not None:
+        ids = {lib.moe_kernel_name(i).decode(): i for i in range(MOE_K_COUNT)}
+        mask = 0
+        for n in names:
+            mask |= 1 << ids[n]
+    _check(lib.moe_profile_filter(mask), "moe_profile_filter")
 
 
 def moe_profile_read():

@@ -6,6 +6,7 @@
 namespace moe {
 
 bool g_prof_on = false;
+uint32_t g_prof_mask = 0xffffffffu;
 
 namespace {
 struct Rec { int id; hipEvent_t a, b; };
@@ -15,6 +16,7 @@ bool g_open = false;   // a begin mark was taken and awaits its end mark
 }  // namespace
 
 void prof_mark(int kernel_id, hipStream_t s, bool begin) {
+  if (!(g_prof_mask >> kernel_id & 1u)) return;
   if (begin) {
     if (g_used >= g_pool.size()) { g_open = false; return; }
     g_pool[g_used].id = kernel_id;
@@ -47,6 +49,11 @@ moe_status moe_profile_enable(int32_t max_records) {
       return MOE_ERR_DEVICE;
   }
   g_prof_on = true;
+  return MOE_OK;
+}
+
+moe_status moe_profile_filter(uint32_t mask) {
+  g_prof_mask = mask;
   return MOE_OK;
 }
 
