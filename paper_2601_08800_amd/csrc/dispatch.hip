@@ -5,7 +5,8 @@
 //   1. hist    one wavefront per sub-chunk of 64 consecutive assignments counts
 //              them per local expert with ballots (no atomics)
 //   2. scan    per expert (one wavefront each) an exclusive scan over the
-//              sub-chunks -> counts; then offsets = exclusive scan over experts
+//              sub-chunks -> counts; offsets = exclusive scan over experts,
+//              rebuilt in LDS by every scatter workgroup
 //   3. scatter the same ballots give every assignment its rank inside its
 //              sub-chunk; position = offsets[e] + start of sub-chunk + rank
 //   4. gather  one wavefront per token reads the row ONCE (16 B per lane,
@@ -41,8 +42,37 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
 template <int MODE>
 __global__ __launch_bounds__(256) void dispatch_index_kernel(
     const int32_t* __restrict__ ids, int A, int e_lo, int E_loc, int n_sub,
-    int32_t* __restrict__ hist, const int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
-    int32_t* __restrict__ inv) {
+    int32_t* __restrict__ hist, const int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets_out, int32_t* __restrict__ perm, int32_t* __restrict__ inv) {
+  // MODE 1: every workgroup rebuilds offsets = exclusive scan of counts in LDS
+  // (E_loc <= 512 values, one wavefront); workgroup 0 also stores them.
+  __shared__ int32_t offsets[513];
+  if (MODE == 1) {
+    if (threadIdx.x < 64) {
+      const int l = threadIdx.x;
+      const int per = (E_loc + 63) / 64;
+      const int x0 = l * per, x1 = (x0 + per < E_loc) ? x0 + per : E_loc;
+      int sum = 0;
+      for (int x = x0; x < x1; ++x) sum += counts[x];
+      int incl = sum;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (l >= off) incl += o;
+      }
+      int run = incl - sum;
+      for (int x = x0; x < x1; ++x) {
+        offsets[x] = run;
+        if (blockIdx.x == 0) offsets_out[x] = run;
+        run += counts[x];
+      }
+      if (l == 63) {
+        offsets[E_loc] = incl;
+        if (blockIdx.x == 0) offsets_out[E_loc] = incl;
+      }
+    }
+    __syncthreads();
+  }
   const int lane = threadIdx.x & 63;
   const int sub = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (sub >= n_sub) return;
@@ -107,29 +137,6 @@ __global__ __launch_bounds__(64) void dispatch_scan_kernel(int32_t* __restrict__
   if (lane == 63) counts[e] = incl;
 }
 
-// One wavefront: offsets = exclusive scan of counts (E_loc <= 512).
-__global__ __launch_bounds__(64) void dispatch_offsets_kernel(const int32_t* __restrict__ counts,
-                                                             int E_loc,
-                                                             int32_t* __restrict__ offsets) {
-  const int lane = threadIdx.x;
-  const int per = (E_loc + 63) / 64;
-  const int e0 = lane * per, e1 = (e0 + per < E_loc) ? e0 + per : E_loc;
-  int sum = 0;
-  for (int e = e0; e < e1; ++e) sum += counts[e];
-  int incl = sum;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int o = __shfl_up(incl, off);
-    if (lane >= off) incl += o;
-  }
-  int run = incl - sum;
-  for (int e = e0; e < e1; ++e) {
-    offsets[e] = run;
-    run += counts[e];
-  }
-  if (lane == 63) offsets[E_loc] = incl;
-}
-
 // One wavefront per token: read the row once, write it to every local position.
 // `row16` = row length in 16-byte pieces.
 template <int PIECES>
@@ -178,13 +185,11 @@ hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int3
   const int n_sub = (A + kSub - 1) / kSub;
   const dim3 grid_idx((n_sub + 3) / 4), block_idx(256);
   MOE_LAUNCH(MOE_K_DISPATCH_HIST, dispatch_index_kernel<0>, grid_idx, block_idx, 0, s, ids, A,
-             c.expert_lo, E_loc, n_sub, ws.block_hist, (const int32_t*)nullptr, perm, inv);
+             c.expert_lo, E_loc, n_sub, ws.block_hist, (const int32_t*)nullptr, offsets, perm, inv);
   MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_scan_kernel, dim3(E_loc), dim3(64), 0, s, ws.block_hist,
              n_sub, counts);
-  MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_offsets_kernel, dim3(1), dim3(64), 0, s, counts, E_loc,
-             offsets);
   MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_index_kernel<1>, grid_idx, block_idx, 0, s, ids, A,
-             c.expert_lo, E_loc, n_sub, ws.block_hist, offsets, perm, inv);
+             c.expert_lo, E_loc, n_sub, ws.block_hist, counts, offsets, perm, inv);
   const int row16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
   MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_gather_kernel<8>, dim3((T + 3) / 4), dim3(256), 0, s,
                      static_cast<const uint4*>(x), inv, static_cast<uint4*>(xs), T, k, row16);

@@ -556,6 +556,158 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
   }
 }
 
+// ----------------------------------------- MFMA GEMM, weight streaming (decode)
+// Few rows per expert: the work is reading every weight once.  Tile = 32 rows x
+// 64 weight rows (DUAL: 32 gate + the matching 32 up rows); the four wavefronts
+// of a workgroup split K between them (wavefront w takes K slices w, w+4, ...,
+// a slice being 128 bytes of every weight row: 64 bf16 or 128 e4m3 values), each
+// with its own register-staged pipeline: no LDS, no barrier until the partial
+// sums are added in a fixed order at the end.  Many small workgroups (n tiles of
+// 32 / 64 columns) and two slices of loads in flight per wavefront keep all of
+// HBM busy even when a single expert holds most rows; M tiles of one expert are
+// neighbours in the grid, so its weights are read from HBM once.
+// Inside a slice, MFMA sub-step kk of lane half h covers k = h*W/2 + kk*8 .. +8
+// (W = slice width) for BOTH operands, so every lane reads one contiguous run.
+template <bool DUAL, bool FP8>
+__global__ __launch_bounds__(256) void ffn_skinny_kernel(
+    const uint16_t* __restrict__ A, const void* __restrict__ B0, const void* __restrict__ B1,
+    const float* __restrict__ S0, const float* __restrict__ S1, uint16_t* __restrict__ C, int N,
+    int K, const int32_t* __restrict__ tiles) {
+  constexpr int W = FP8 ? 128 : 64;          // K values per slice
+  constexpr int NKK = W / 16;                // MFMA sub-steps per slice
+  constexpr int BN = DUAL ? 32 : 64;         // output columns per workgroup
+  constexpr int BL = FP8 ? NKK / 2 : NKK;    // 16-byte loads per lane, slice and weight block
+  __shared__ float red[4][2][16][64];        // partial sums of the four wavefronts
+
+  const int n_ntiles = (N + BN - 1) / BN;
+  const int total = tiles[0] * n_ntiles;
+  if (int(blockIdx.x) >= total) return;
+  int mtile = blockIdx.x / n_ntiles;
+  const int first = tiles[4 + kTileRec * mtile], cnt = tiles[5 + kTileRec * mtile];
+  const int local = blockIdx.x - first * n_ntiles;      // inside the expert: M tile fastest
+  const int ntile = local / cnt;
+  mtile = first + (local - ntile * cnt);
+  const int e = tiles[1 + kTileRec * mtile], row0 = tiles[2 + kTileRec * mtile],
+            row1 = tiles[3 + kTileRec * mtile];
+  const int n0 = ntile * BN;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int h = lane >> 5;
+  const size_t wb = FP8 ? 1 : 2;
+  // this lane's rows: activation row, and the weight row of each of the two blocks
+  int ar = row0 + (lane & 31);
+  ar = ar < row1 ? ar : row1 - 1;
+  const uint16_t* arow = A + size_t(ar) * K + h * (W / 2);
+  const char* brow[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    int n = n0 + (DUAL ? 0 : j * 32) + (lane & 31);
+    n = n < N ? n : N - 1;
+    const char* base = static_cast<const char*>((DUAL && j == 1) ? B1 : B0) + size_t(e) * N * K * wb;
+    brow[j] = base + (size_t(n) * K + h * (W / 2)) * wb;
+  }
+
+  f32x16 acc[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[j][q] = 0.f;
+
+  struct Slice { uint4 a[NKK]; uint4 b[2][BL]; };
+  auto load = [&](int sl, Slice& r) {
+    const int k0 = sl * W;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) r.a[kk] = *reinterpret_cast<const uint4*>(arow + k0 + kk * 8);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < BL; ++q)
+        r.b[j][q] = *reinterpret_cast<const uint4*>(brow[j] + size_t(k0) * wb + q * 16);
+  };
+  auto compute = [&](int sl, const Slice& r) {
+    if constexpr (FP8) {
+      // one scale block along K per slice; the 32 columns lie inside one block
+      const int nkb = (K + 127) / 128, nnb = (N + 127) / 128;
+      f32x16 part[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) part[j][q] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+          // eight codes of this sub-step -> eight bf16 (exact)
+          const uint4 v = r.b[j][kk >> 1];
+          const uint32_t c0 = (kk & 1) ? v.z : v.x, c1 = (kk & 1) ? v.w : v.y;
+          const f32x2 p0 = __builtin_amdgcn_cvt_pk_f32_fp8(c0, false), p1 = __builtin_amdgcn_cvt_pk_f32_fp8(c0, true);
+          const f32x2 p2 = __builtin_amdgcn_cvt_pk_f32_fp8(c1, false), p3 = __builtin_amdgcn_cvt_pk_f32_fp8(c1, true);
+          const uint4 w8 = make_uint4((__float_as_uint(p0[0]) >> 16) | (__float_as_uint(p0[1]) & 0xffff0000u),
+                                      (__float_as_uint(p1[0]) >> 16) | (__float_as_uint(p1[1]) & 0xffff0000u),
+                                      (__float_as_uint(p2[0]) >> 16) | (__float_as_uint(p2[1]) & 0xffff0000u),
+                                      (__float_as_uint(p3[0]) >> 16) | (__float_as_uint(p3[1]) & 0xffff0000u));
+          part[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, r.a[kk]),
+                                                            __builtin_bit_cast(bf16x8, w8), part[j], 0, 0, 0);
+        }
+        int n = n0 + (DUAL ? 0 : j * 32);
+        n = n < N ? n : N - 1;
+        const float* S = (DUAL && j == 1) ? S1 : S0;
+        const float sc = S[(size_t(e) * nnb + n / 128) * nkb + sl];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[j][q] = fmaf(sc, part[j][q], acc[j][q]);
+      }
+    } else {
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, r.a[kk]),
+                                                           __builtin_bit_cast(bf16x8, r.b[j][kk]),
+                                                           acc[j], 0, 0, 0);
+    }
+  };
+
+  const int nslices = K / W;
+  Slice r0, r1;
+  int sl = wave;
+  if (sl < nslices) load(sl, r0);
+  while (sl < nslices) {                     // two slices per trip: r0 and r1 alternate
+    if (sl + 4 < nslices) load(sl + 4, r1);
+    compute(sl, r0);
+    sl += 4;
+    if (sl >= nslices) break;
+    if (sl + 4 < nslices) load(sl + 4, r0);
+    compute(sl, r1);
+    sl += 4;
+  }
+
+  // add the four partial sums in a fixed order: wavefront w finishes registers 4w..4w+3
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) red[wave][j][q][lane] = acc[j][q];
+  __syncthreads();
+#pragma unroll
+  for (int qq = 0; qq < 4; ++qq) {
+    const int q = wave * 4 + qq;
+    float v[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      v[j] = ((red[0][j][q][lane] + red[1][j][q][lane]) + red[2][j][q][lane]) + red[3][j][q][lane];
+    // D layout: lane l, register q -> row (q/4)*8 + (l/32)*4 + q%4, col l%32
+    const int row = row0 + (q >> 2) * 8 + (lane >> 5) * 4 + (q & 3);
+    if (row >= row1) continue;
+    if (DUAL) {
+      const int col = n0 + (lane & 31);
+      if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(silu_mul(v[0], v[1]));
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = n0 + j * 32 + (lane & 31);
+        if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(v[j]);
+      }
+    }
+  }
+}
+
 // ------------------------------------------------------------ fp32 GEMM
 // Plain VALU kernel for the fp32 configuration: 64x64 tile, 16x16 threads,
 // 4x4 outputs per thread, K step 16.
@@ -651,6 +803,24 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
                      (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
 }
 
+template <bool FP8>
+void launch_skinny(const moe_config& c, int n_experts, const void* xs, const int32_t* offsets,
+                   int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
+                   const float* s_gate, const float* s_up, const float* s_down, void* ys,
+                   const FfnWs& ws, hipStream_t s) {
+  const int H = c.hidden, I = c.inter_local;
+  const int max_mt = rows_capacity / 32 + n_experts;
+  MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, 32,
+             rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0);
+  const int nt1 = (I + 31) / 32, nt2 = (H + 63) / 64;
+  MOE_LAUNCH(MOE_K_FFN_GEMM1, (ffn_skinny_kernel<true, FP8>), dim3(size_t(max_mt) * nt1), dim3(256),
+             0, s, static_cast<const uint16_t*>(xs), w_gate, w_up, s_gate, s_up,
+             static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
+  MOE_LAUNCH(MOE_K_FFN_GEMM2, (ffn_skinny_kernel<false, FP8>), dim3(size_t(max_mt) * nt2), dim3(256),
+             0, s, static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr, s_down,
+             (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
+}
+
 void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const int32_t* offsets,
                     int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
                     void* ys, const FfnWs& ws, hipStream_t s) {
@@ -709,10 +879,12 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
   const int avg = rows_capacity / n_experts;
   const bool fp8 = c.weight_dtype == MOE_FP8_E4M3_B128;
 #define MOE_FFN_ARGS c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, s_gate, s_up, s_down, ys, ws, s
-  if (fp8) {
-    // weight streaming: the 32-row variant keeps four workgroups per CU in
-    // flight, which is what hides the HBM latency of its register-staged loads
+  if (fp8 && H % 128 == 0 && I % 128 == 0) {
+    launch_skinny<true>(MOE_FFN_ARGS);
+  } else if (fp8) {
     launch_mfma_pair<32, 128, 32, 32, 256, 64, true>(MOE_FFN_ARGS);
+  } else if (avg <= 32 && H % 64 == 0 && I % 64 == 0) {
+    launch_skinny<false>(MOE_FFN_ARGS);
   } else if (avg <= 32) {
     launch_mfma_pair<32, 128, 32, 32, 256, 64, false>(MOE_FFN_ARGS);
   } else if (avg <= 64) {
