@@ -2,13 +2,13 @@
 //
 // A stable counting sort of the local assignments by expert, with no atomics
 // anywhere (so the permutation is unique and repeatable):
-//   1. hist    one wavefront per sub-chunk of 64 consecutive assignments counts
-//              them per local expert with ballots (no atomics)
+//   1. count   one wavefront per sub-chunk of 64 consecutive assignments counts
+//              them per local expert with ballots (no atomics) and notes every
+//              assignment's rank among its expert's assignments of the sub-chunk
 //   2. scan    per expert (one wavefront each) an exclusive scan over the
 //              sub-chunks -> counts; offsets = exclusive scan over experts,
 //              rebuilt in LDS by every scatter workgroup
-//   3. scatter the same ballots give every assignment its rank inside its
-//              sub-chunk; position = offsets[e] + start of sub-chunk + rank
+//   3. place   position = offsets[e] + start of the sub-chunk's run + rank
 //   4. gather  one wavefront per token reads the row ONCE (16 B per lane,
 //              coalesced) and writes it to each of its local positions
 #include "moe_internal.h"
@@ -36,80 +36,80 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
 
 // One wavefront per sub-chunk of 64 consecutive flat assignments.  The lanes
 // that go to the same local expert find each other with ballots (one round per
-// distinct expert present), which yields the count per expert (MODE 0) or the
-// rank of every assignment among its expert's assignments of the sub-chunk
-// (MODE 1) without atomics.  hist is [E_loc][n_sub].
-template <int MODE>
-__global__ __launch_bounds__(256) void dispatch_index_kernel(
+// distinct expert present), which yields, without atomics, the count per expert
+// and the rank of every assignment among its expert's assignments of the
+// sub-chunk.  Counts go to hist[E_loc][n_sub] (built in a wavefront-private LDS
+// row, so absent experts get their zero), ranks are parked in inv[].
+__global__ __launch_bounds__(256) void dispatch_count_kernel(
     const int32_t* __restrict__ ids, int A, int e_lo, int E_loc, int n_sub,
-    int32_t* __restrict__ hist, const int32_t* __restrict__ counts,
-    int32_t* __restrict__ offsets_out, int32_t* __restrict__ perm, int32_t* __restrict__ inv) {
-  // MODE 1: every workgroup rebuilds offsets = exclusive scan of counts in LDS
-  // (E_loc <= 512 values, one wavefront); workgroup 0 also stores them.
-  __shared__ int32_t offsets[513];
-  if (MODE == 1) {
-    if (threadIdx.x < 64) {
-      const int l = threadIdx.x;
-      const int per = (E_loc + 63) / 64;
-      const int x0 = l * per, x1 = (x0 + per < E_loc) ? x0 + per : E_loc;
-      int sum = 0;
-      for (int x = x0; x < x1; ++x) sum += counts[x];
-      int incl = sum;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off);
-        if (l >= off) incl += o;
-      }
-      int run = incl - sum;
-      for (int x = x0; x < x1; ++x) {
-        offsets[x] = run;
-        if (blockIdx.x == 0) offsets_out[x] = run;
-        run += counts[x];
-      }
-      if (l == 63) {
-        offsets[E_loc] = incl;
-        if (blockIdx.x == 0) offsets_out[E_loc] = incl;
-      }
-    }
-    __syncthreads();
-  }
-  const int lane = threadIdx.x & 63;
-  const int sub = blockIdx.x * 4 + (threadIdx.x >> 6);
+    int32_t* __restrict__ hist, int32_t* __restrict__ inv) {
+  __shared__ int32_t cnt[4][512];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = blockIdx.x * 4 + wave;
   if (sub >= n_sub) return;
   const int a = sub * kSub + lane;
   int e = -1;
   if (a < A) {
     e = ids[a] - e_lo;
-    if (e < 0 || e >= E_loc) {
-      e = -1;
-      if (MODE == 1) inv[a] = -1;
-    }
+    if (e < 0 || e >= E_loc) e = -1;
   }
-  uint64_t present[8] = {0, 0, 0, 0, 0, 0, 0, 0};   // experts seen in this sub-chunk (E_loc <= 512)
+  int32_t* row = cnt[wave];                    // same-wavefront LDS accesses execute in order
+  for (int x = lane; x < E_loc; x += 64) row[x] = 0;
+  int rank = -1;
   uint64_t todo = __ballot(e >= 0);
   while (todo) {                               // one round per distinct expert
     const int leader = __ffsll((unsigned long long)todo) - 1;
     const int e0 = __shfl(e, leader);
     const uint64_t m = __ballot(e == e0);
-    if (MODE == 0) {
-      if (lane == leader) hist[size_t(e0) * n_sub + sub] = __popcll(m);
-#pragma unroll
-      for (int q = 0; q < 8; ++q)
-        if ((e0 >> 6) == q) present[q] |= uint64_t(1) << (e0 & 63);
-    } else if (e == e0) {
-      const int pos = hist[size_t(e0) * n_sub + sub] + offsets[e0] + __popcll(m & lanemask_lt());
-      perm[pos] = a;
-      inv[a] = pos;
-    }
+    if (e == e0) rank = __popcll(m & lanemask_lt());
+    if (lane == leader) row[e0] = __popcll(m);
     todo &= ~m;
   }
-  if (MODE == 0) {                             // the other experts have no assignment here
+  if (a < A) inv[a] = rank;                    // -1: expert not local
+  for (int x = lane; x < E_loc; x += 64) hist[size_t(x) * n_sub + sub] = row[x];
+}
+
+// Position of every local assignment: offsets[e] + start of its sub-chunk's run
+// inside the expert's segment + its rank (left in inv[] by the count kernel).
+// Every workgroup rebuilds offsets = exclusive scan of counts in LDS (E_loc <=
+// 512 values, one wavefront); workgroup 0 also stores them.
+__global__ __launch_bounds__(256) void dispatch_place_kernel(
+    const int32_t* __restrict__ ids, int A, int e_lo, int E_loc, int n_sub,
+    const int32_t* __restrict__ hist, const int32_t* __restrict__ counts,
+    int32_t* __restrict__ offsets_out, int32_t* __restrict__ perm, int32_t* __restrict__ inv) {
+  __shared__ int32_t offsets[513];
+  if (threadIdx.x < 64) {
+    const int l = threadIdx.x;
+    const int per = (E_loc + 63) / 64;
+    const int x0 = l * per, x1 = (x0 + per < E_loc) ? x0 + per : E_loc;
+    int sum = 0;
+    for (int x = x0; x < x1; ++x) sum += counts[x];
+    int incl = sum;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int x = q * 64 + lane;
-      if (x < E_loc && !(present[q] >> lane & 1)) hist[size_t(x) * n_sub + sub] = 0;
+    for (int off = 1; off < 64; off <<= 1) {
+      const int o = __shfl_up(incl, off);
+      if (l >= off) incl += o;
+    }
+    int run = incl - sum;
+    for (int x = x0; x < x1; ++x) {
+      offsets[x] = run;
+      if (blockIdx.x == 0) offsets_out[x] = run;
+      run += counts[x];
+    }
+    if (l == 63) {
+      offsets[E_loc] = incl;
+      if (blockIdx.x == 0) offsets_out[E_loc] = incl;
     }
   }
+  __syncthreads();
+  const int a = blockIdx.x * 256 + threadIdx.x;
+  if (a >= A) return;
+  const int rank = inv[a];
+  if (rank < 0) return;                        // inv[a] stays -1
+  const int e = ids[a] - e_lo;
+  const int pos = offsets[e] + hist[size_t(e) * n_sub + a / kSub] + rank;
+  perm[pos] = a;
+  inv[a] = pos;
 }
 
 // One wavefront per local expert: exclusive scan of the expert's row of counts
@@ -184,12 +184,12 @@ hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int3
   const int E_loc = c.expert_hi - c.expert_lo;
   const int n_sub = (A + kSub - 1) / kSub;
   const dim3 grid_idx((n_sub + 3) / 4), block_idx(256);
-  MOE_LAUNCH(MOE_K_DISPATCH_HIST, dispatch_index_kernel<0>, grid_idx, block_idx, 0, s, ids, A,
-             c.expert_lo, E_loc, n_sub, ws.block_hist, (const int32_t*)nullptr, offsets, perm, inv);
+  MOE_LAUNCH(MOE_K_DISPATCH_HIST, dispatch_count_kernel, grid_idx, block_idx, 0, s, ids, A,
+             c.expert_lo, E_loc, n_sub, ws.block_hist, inv);
   MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_scan_kernel, dim3(E_loc), dim3(64), 0, s, ws.block_hist,
              n_sub, counts);
-  MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_index_kernel<1>, grid_idx, block_idx, 0, s, ids, A,
-             c.expert_lo, E_loc, n_sub, ws.block_hist, counts, offsets, perm, inv);
+  MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_place_kernel, dim3((A + 255) / 256), block_idx, 0, s,
+             ids, A, c.expert_lo, E_loc, n_sub, ws.block_hist, counts, offsets, perm, inv);
   const int row16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
   MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_gather_kernel<8>, dim3((T + 3) / 4), dim3(256), 0, s,
                      static_cast<const uint4*>(x), inv, static_cast<uint4*>(xs), T, k, row16);
