@@ -18,11 +18,12 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
 // route
 constexpr int kRouteCounterBytes = 256;       // [0]=tokens re-scored in fp64
+constexpr int kGateMaxSplit = 4;              // K splits of the gate GEMM when few tokens leave CUs idle
 constexpr int kGateChainSteps = 1;            // K-steps of 64 per fp32 accumulation chain
 struct RouteWs {
   int32_t* counters;   // [64]
-  float* logits;       // [T,E] fast logits (fp32)
-  float* xnorm2;       // [T] sum of squares of the token row
+  float* logits;       // [kGateMaxSplit][T,E] fast logits (fp32), one slab per K split
+  float* xnorm2;       // [kGateMaxSplit][T] sum of squares of the token row, per K split
   float* wnorm2;       // [E] sum of squares of the gate row
   int32_t* recheck;    // [T] token ids to re-score (bit 30 set: all experts)
   size_t bytes;

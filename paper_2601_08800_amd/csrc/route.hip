@@ -212,14 +212,21 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN;
-  const int ksteps = (H + GBK - 1) / GBK;
+  // K split: slab z of gridDim.z covers K steps [z*per, (z+1)*per) and writes its own
+  // partial logits and partial row norms
+  const int all_steps = (H + GBK - 1) / GBK;
+  const int per_split = (all_steps + gridDim.z - 1) / gridDim.z;
+  const int ks0 = blockIdx.z * per_split;
+  const int ksteps = (ks0 + per_split < all_steps ? ks0 + per_split : all_steps) - ks0;
+  logits += size_t(blockIdx.z) * T * E;
+  xnorm2 += size_t(blockIdx.z) * T;
 
   // global -> register staging: A 2 pieces / thread, B 4 pieces / thread
   const int lrow = tid >> 3, lpiece = tid & 7;
   uint4 ra[2], rb[4];
   float xsq[2] = {0.f, 0.f};
   auto gload = [&](int ks) {
-    const int kcol = ks * GBK + lpiece * 8;
+    const int kcol = (ks0 + ks) * GBK + lpiece * 8;
     const bool kin = kcol < H;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -314,7 +321,17 @@ struct SelCfg {
   float scale;
   float chain_err;   // 2n * 2^-24 of the gate accumulation (0 when logits are given)
   int have_norms;
+  int nsplit;        // K splits of the gate GEMM: logits and row norms are sums of this many slabs
+  int T;             // tokens: slab strides are T*E (logits) and T (row norms)
 };
+
+// Norm of token t's row from the per-split sums of squares.
+__device__ __forceinline__ float token_norm(const SelCfg& c, const float* __restrict__ xnorm2, int t) {
+  if (!c.have_norms) return 0.f;
+  float s = xnorm2[t];
+  for (int i = 1; i < c.nsplit; ++i) s += xnorm2[t + size_t(i) * c.T];
+  return sqrtf(s);
+}
 
 // Per-lane view of one token's experts: expert e = slot*64 + lane.
 template <typename FT, int EPL>
@@ -352,6 +369,7 @@ __device__ __forceinline__ void fast_keys(const SelCfg& c, const float* __restri
     float key = -INFINITY, eps = 0.f, sc = 0.f;
     if (e < c.E) {
       float z = logits_row[e];
+      for (int sp = 1; sp < c.nsplit; ++sp) z += logits_row[e + size_t(sp) * c.T * c.E];
       float ez = 0.f;
       if (c.have_norms) ez = c.chain_err * xn * sqrtf(wnorm2[e]) * 1.001f + 2.f * kUlp * fabsf(z);
       if (logit_bias) {
@@ -561,7 +579,7 @@ __global__ __launch_bounds__(256) void route_select_kernel(
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
   Keys<float, EPL> K;
-  const float xn = c.have_norms ? sqrtf(xnorm2[t]) : 0.f;
+  const float xn = token_norm(c, xnorm2, t);
   fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
   Groups<float> Gp;
   Gp.kept = 0; Gp.certain = true; Gp.need = 0;
@@ -694,7 +712,7 @@ __global__ __launch_bounds__(256) void route_recheck_kernel(
       exact |= want;
     };
     if (wave == 0) {
-      const float xn = c.have_norms ? sqrtf(xnorm2[t]) : 0.f;
+      const float xn = token_norm(c, xnorm2, t);
       fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
@@ -777,7 +795,7 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   SelCfg sc;
   sc.E = E; sc.k = c.top_k; sc.score_fn = c.score_fn; sc.renormalize = c.renormalize;
   sc.G = c.n_groups; sc.Kg = c.topk_groups; sc.gn = c.group_score_n; sc.scale = c.routed_scale;
-  sc.chain_err = 0.f; sc.have_norms = 0;
+  sc.chain_err = 0.f; sc.have_norms = 0; sc.nsplit = 1; sc.T = T;
   const void* gw_for_norm = logits_in ? nullptr : gate_w;
   if (bf16)
     MOE_LAUNCH(MOE_K_GATE_NORMS, gate_wnorm_kernel<true>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm, E,
@@ -792,12 +810,22 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
     // microseconds up to about 2^28 of them, and needs (almost) no re-scoring
     const bool small = size_t(T) * E * H <= (size_t(1) << 28);
     if (bf16 && !small) {
-      const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN);
+      // fewer tiles than CUs: split K so that about one workgroup per CU runs; each
+      // split keeps at least 8 K steps
+      const int blocks = ((T + GBM - 1) / GBM) * ((E + GBN - 1) / GBN);
+      const int ksteps = (H + GBK - 1) / GBK;
+      int nsplit = 1;
+      while (nsplit < kGateMaxSplit && blocks * nsplit * 2 <= 256 && ksteps / (nsplit * 2) >= 8) nsplit *= 2;
+      const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN, nsplit);
       MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(256), 0, s,
                  static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
                  ws.logits, ws.xnorm2);
-      // chains of kGateChainSteps*64 products; +2 for the flush and the store
-      sc.chain_err = (2.f * kGateChainSteps * GBK + 2.f) * kUlp;
+      sc.nsplit = nsplit;
+      // chains of kGateChainSteps*64 products; +2 for the flush and the store.  The
+      // partial dot products of the splits obey sum_s |x_s||w_s| <= |x||w|, so the
+      // chain term is unchanged; summing the slabs in fp32 adds one ulp of that
+      // product per addition and per slab store
+      sc.chain_err = (2.f * kGateChainSteps * GBK + 2.f + 2.f * (nsplit - 1)) * kUlp;
     } else {
       if (bf16)
         MOE_LAUNCH(MOE_K_GATE_GEMM, gate_f64_kernel<true>, dim3(T), dim3(256), 0, s, x, gate_w, T,
