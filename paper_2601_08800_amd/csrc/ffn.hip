@@ -16,6 +16,9 @@
 // and u of the same element and the SwiGLU is applied in registers.
 // fp8 weights: e4m3 codes are widened to bf16 (exact) on the way into LDS; the
 // 128x128 block scale multiplies the fp32 partial sum of each 128-deep K block.
+#include <cstdlib>
+#include <type_traits>
+
 #include "moe_internal.h"
 
 namespace moe {
@@ -34,6 +37,13 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   return __builtin_bit_cast(uint16_t, (__bf16)f);   // round to nearest even
 }
 
+// silu(g) * u with the hardware exp2 and reciprocal (1 ulp each): the result is
+// rounded to bf16 right after
+__device__ __forceinline__ float silu_mul_fast(float g, float u) {
+  const float t = __builtin_amdgcn_exp2f(g * -1.44269504088896341f);
+  return g * u * __builtin_amdgcn_rcpf(1.0f + t);
+}
+
 __device__ __forceinline__ float silu_mul(float g, float u) {
   return g / (1.0f + __expf(-g)) * u;
 }
@@ -42,6 +52,12 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 // tiles[0] = number of M tiles; then per tile a record (expert, first row, end
 // row, index of the expert's first tile, number of tiles of the expert).
 constexpr int kTileRec = 5;
+#ifndef MOE_SPREAD_SLOTS
+#define MOE_SPREAD_SLOTS 3
+#endif
+#ifndef MOE_RING_EXTRA_A
+#define MOE_RING_EXTRA_A 2
+#endif
 // `balance`: an expert's rows are cut into ceil(M/bm) tiles of equal height
 // (rounded up to 32 rows) instead of full tiles plus a short tail.
 __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restrict__ offsets,
@@ -328,13 +344,25 @@ __device__ __forceinline__ int swz2(int row, int piece) {
 // moves whole cache lines.  (A K step of 32 would allow four stages for the tall
 // tiles too, but its 64-byte row pieces halve the efficiency of the load path:
 // measured 8 % slower on the 256-row tiles.)
+#ifdef MOE_GEMM_TRACE
+__device__ unsigned long long g_trace[16][160][4];
+__device__ unsigned long long g_tile[8192][4];   // per workgroup: hw id, wall clock at entry / after K loop / at exit
+#define MOE_STAMP(i) do { if (tr_slot >= 0 && ks < 160) { g_trace[tr_slot][ks][i] = __builtin_readcyclecounter(); } } while (0)
+#else
+#define MOE_STAMP(i) do {} while (0)
+#endif
 template <int NB> struct Ring {
   static constexpr int kBK = 64;
   static constexpr int kPPR = kBK / 8;                              // 16-byte pieces per row
   static constexpr int kARows = NB * 32;
-  static constexpr int kStageSlots = (kARows + 256) * kPPR;
-  static constexpr int kFit = (160 * 1024 - 4096) / (kStageSlots * 16);
-  static constexpr int kStages = kFit > 4 ? 4 : kFit;
+  static constexpr int kASlots = kARows * kPPR;                     // 16-byte slots of an A stage
+  static constexpr int kBSlots = 256 * kPPR;                        // ... of a B stage
+  static constexpr int kLds = 160 * 1024;
+  static constexpr int kFit = kLds / ((kASlots + kBSlots) * 16);
+  static constexpr int kSB = kFit > 4 ? 4 : kFit;                   // weight stages
+  // LDS left over after kSB whole stages takes further activation stages
+  static constexpr int kMore = (kLds - kSB * (kASlots + kBSlots) * 16) / (kASlots * 16);
+  static constexpr int kSA = kSB + (kMore > MOE_RING_EXTRA_A ? MOE_RING_EXTRA_A : kMore);
 };
 
 template <bool DUAL, int NB, int WM>
@@ -344,12 +372,14 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
                                             uint16_t* __restrict__ C, int N, int K, int row0,
                                             int row1, int n0, uint4* smem, int wave) {
   constexpr int NBW = NB - WM * 4 < 0 ? 0 : (NB - WM * 4 > 4 ? 4 : NB - WM * 4);
-  constexpr int S = Ring<NB>::kStages;
-  constexpr int SS = Ring<NB>::kStageSlots;
+  constexpr int SA = Ring<NB>::kSA, SB = Ring<NB>::kSB;
   constexpr int KS = Ring<NB>::kBK;                  // K step
   constexpr int PPR = Ring<NB>::kPPR;                // pieces per LDS row: 8 or 4
   constexpr int RPI = 64 / PPR;                      // rows filled by one load instruction
-  constexpr int AS = Ring<NB>::kARows * PPR;         // slots of the A part of a stage
+  constexpr int AS = Ring<NB>::kASlots;              // slots of an A stage
+  constexpr int BS = Ring<NB>::kBSlots;              // slots of a B stage
+  uint4* const ringA = smem;
+  uint4* const ringB = smem + SA * AS;
   const int lane = threadIdx.x & 63;
   const int wn = wave & 3;
   const int ksteps = K / KS;
@@ -390,9 +420,9 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     bsrc[q] = base + size_t(n) * K + piece * 8;
   }
   const bool extra = AREM > 0 && wave < AREM;        // this wavefront loads one more A row group
-  auto issue = [&](int ks) {
+  auto issue_a = [&](int ks) {
     const int kcol = ks * KS;
-    uint4* st = smem + (ks % S) * SS;
+    uint4* st = ringA + (ks % SA) * AS;
 #pragma unroll
     for (int q = 0; q < NAQ; ++q)
       __builtin_amdgcn_global_load_lds((gptr_t)(asrc[q] + kcol), (lptr_t)(st + (q * 8 + wave) * 64),
@@ -400,21 +430,26 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     if (extra)
       __builtin_amdgcn_global_load_lds((gptr_t)(asrc[NAQ] + kcol),
                                        (lptr_t)(st + (NAQ * 8 + wave) * 64), 16, 0, 0);
+  };
+  auto issue_b = [&](int ks) {
+    const int kcol = ks * KS;
+    uint4* st = ringB + (ks % SB) * BS;
 #pragma unroll
     for (int q = 0; q < NBQ; ++q)
       __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[q] + kcol),
-                                       (lptr_t)(st + AS + (q * 8 + wave) * 64), 16, 0, 0);
+                                       (lptr_t)(st + (q * 8 + wave) * 64), 16, 0, 0);
   };
-  // wait until at most `steps` younger steps of this wavefront's loads are in flight
-  constexpr int LPS = NAQ + NBQ;
-  auto wait_steps = [&](int steps) {
-    if (S >= 4 && steps >= 2) {
-      if (extra) wait_vmcnt<2 * (LPS + 1)>(); else wait_vmcnt<2 * LPS>();
-    } else if (S >= 3 && steps >= 1) {
-      if (extra) wait_vmcnt<LPS + 1>(); else wait_vmcnt<LPS>();
-    } else {
-      wait_vmcnt<0>();
-    }
+  // Issue group of step g (after its barrier): weights of step g+SB-1, then
+  // activations of step g+SA-1 (SA >= SB).  Loads return in order, so at the
+  // barrier of step ks everything younger than the weights of step ks may stay in
+  // flight: the activation part of group ks-SB+1 (when SA > SB) and the SB-2 whole
+  // groups after it.  Near the end of K, where groups shrink, wait for all.
+  constexpr int YA = SA > SB ? 1 : 0;
+  constexpr int YG = SB - 2;
+  auto wait_step = [&](bool steady) {
+    if (!steady) wait_vmcnt<0>();
+    else if (extra) wait_vmcnt<YA * (NAQ + 1) + YG * (NAQ + 1 + NBQ)>();
+    else wait_vmcnt<YA * NAQ + YG * (NAQ + NBQ)>();
   };
 
   constexpr int NA = NBW > 0 ? NBW : 1;
@@ -432,20 +467,80 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   constexpr int NKK = KS / 16;                       // MFMA sub-steps per K step
 
 #pragma unroll
-  for (int p = 0; p < S - 1; ++p)
-    if (p < ksteps) issue(p);
-  for (int ks = 0; ks < ksteps; ++ks) {
-    // step ks must have landed; steps ks+1 .. ks+S-2 may still be in flight
-    const int younger = ksteps - 1 - ks;
-    wait_steps(younger < S - 2 ? younger : S - 2);
+  for (int g = 1 - SA; g < 0; ++g) {
+    if (g + SB - 1 >= 0 && g + SB - 1 < ksteps) issue_b(g + SB - 1);
+    if (g + SA - 1 < ksteps) issue_a(g + SA - 1);
+  }
+#ifdef MOE_GEMM_TRACE
+  const bool tr_tile = DUAL && wave == 0 && lane == 0 && blockIdx.x < 8192;
+  if (tr_tile) {
+    g_tile[blockIdx.x][0] = (unsigned long long)__builtin_amdgcn_s_getreg(63492) |
+                            ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32);
+    g_tile[blockIdx.x][1] = wall_clock64();
+  }
+  const int tr_slot = (DUAL && wave == 0 && lane == 0 && blockIdx.x % 64 == 8 && blockIdx.x / 64 < 16) ? int(blockIdx.x / 64) : -1;
+#endif
+  // One load instruction of a step's issue group: ops 0..NBQ-1 are the weight row
+  // groups, NBQ..NBQ+NAQ-1 the activation row groups (weights first: see above).
+  constexpr int NOPS = NBQ + NAQ;
+  auto issue_op = [&](int op, uint4* stb, uint4* sta, int kcb, int kca) {
+    if (op < NBQ)
+      __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[op] + kcb), (lptr_t)(stb + (op * 8 + wave) * 64),
+                                       16, 0, 0);
+    else if (op < NOPS)
+      __builtin_amdgcn_global_load_lds((gptr_t)(asrc[op - NBQ] + kca),
+                                       (lptr_t)(sta + ((op - NBQ) * 8 + wave) * 64), 16, 0, 0);
+  };
+  // One turn of the K loop, rotated by a sub-step so that the synchronisation for
+  // step j sits in front of the LAST sub-step of step j-1:
+  //   wait for the loads of step j, barrier  (every wavefront holds its last
+  //     fragments of step j-1 in registers, so that step's stages are free)
+  //   slot 0: issue loads | read fragments (j, 0) | MFMAs (j-1, 3)
+  //   slot 1: issue loads | read fragments (j, 1) | MFMAs (j, 0)
+  //   slot 2: issue loads | read fragments (j, 2) | MFMAs (j, 1)
+  //   slot 3:               read fragments (j, 3) | MFMAs (j, 2)
+  // The first LDS reads after a barrier are covered by MFMAs that are already
+  // fed, and the load instructions of the step's issue group (which stall a
+  // wavefront until the load path accepts them) are handed out between MFMAs,
+  // ahead of the slot's LDS reads.  SPREAD: the issue group is unconditional (all
+  // but the last SA-1 turns); otherwise it is issued in one go behind a range check.
+  constexpr int NA2 = NA;
+  uint4 fa[2][NA2], fb[2][2];
+#pragma unroll
+  for (int i = 0; i < NA2; ++i) fa[1][i] = make_uint4(0, 0, 0, 0);
+  fb[1][0] = fb[1][1] = make_uint4(0, 0, 0, 0);     // the first turn multiplies zeros
+  auto mfmas = [&](int set) {
+    const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[set][0]);
+    const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[set][1]);
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, fa[set][i]);
+      acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
+      acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
+    }
+  };
+  constexpr int NSLOT = MOE_SPREAD_SLOTS;                    // slots that issue loads
+  constexpr int OPK = (NOPS + NSLOT - 1) / NSLOT;            // load instructions per slot
+  auto turn = [&](int ks, auto spread_c) {
+    constexpr bool SPREAD = decltype(spread_c)::value && NBW > 0;
+    MOE_STAMP(0);
+    // step ks must have landed
+    wait_step(ks + SA - 2 < ksteps);
+    MOE_STAMP(1);
     // a bare barrier (no fence): __syncthreads() would also drain the younger loads
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    // every wavefront has finished step ks-1, so its stage can take step ks+S-1
-    if (ks + S - 1 < ksteps) issue(ks + S - 1);
+    MOE_STAMP(2);
+    // every wavefront has read all of step ks-1, so its stages can be refilled
+    const int kb = ks + SB - 1, ka = ks + SA - 1;
+    uint4* const stb = ringB + (kb % SB) * BS;
+    uint4* const sta = ringA + (ka % SA) * AS;
+    if constexpr (!SPREAD) {
+      if (kb < ksteps) issue_b(kb);
+      if (ka < ksteps) issue_a(ka);
+    }
     if constexpr (NBW > 0) {
-      const uint4* Ab = smem + (ks % S) * SS;
-      const uint4* Bb = Ab + AS;
-      uint4 fa[2][NA], fb[2][2];
+      const uint4* Ab = ringA + (ks % SA) * AS;
+      const uint4* Bb = ringB + (ks % SB) * BS;
       auto read_frags = [&](int kk, int set) {
         const int piece = kk * 2 + (lane >> 5);
         fb[set][0] = Bb[slot(brow0 + (lane & 31), piece)];
@@ -453,53 +548,93 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
 #pragma unroll
         for (int i = 0; i < NBW; ++i) fa[set][i] = Ab[slot(arow + i * 32 + (lane & 31), piece)];
       };
-      read_frags(0, 0);
 #pragma unroll
-      for (int kk = 0; kk < NKK; ++kk) {
-        const int set = kk & 1;
+      for (int sl = 0; sl < NKK; ++sl) {
+        const int set = sl & 1;                              // fragments read in this slot
         __builtin_amdgcn_sched_barrier(0);
-        if (kk < NKK - 1) read_frags(kk + 1, set ^ 1);
-        const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[set][0]);
-        const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[set][1]);
+        if constexpr (SPREAD) {
+          if (sl < NSLOT) {
 #pragma unroll
-        for (int i = 0; i < NBW; ++i) {
-          const bf16x8 a = __builtin_bit_cast(bf16x8, fa[set][i]);
-          acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
-          acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
+            for (int o = 0; o < OPK; ++o)
+              if (sl * OPK + o < NOPS) issue_op(sl * OPK + o, stb, sta, kb * KS, ka * KS);
+          }
         }
-        if (kk < NKK - 1 && NBW >= 2) {
+        read_frags(sl, set);
+        mfmas(set ^ 1);
+        if (NBW >= 2) {
+          // one MFMA, then the loads while no LDS read of this wavefront is
+          // outstanding, then MFMA / LDS read pairs
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (SPREAD && sl < NSLOT) __builtin_amdgcn_sched_group_barrier(0x020, OPK, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
 #pragma unroll
-          for (int i = 0; i < NBW + 2; ++i) {
+          for (int i = 0; i < NBW + 1; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
           }
           __builtin_amdgcn_sched_group_barrier(0x008, 2 * NBW - (NBW + 2), 0);
         }
       }
+      if constexpr (SPREAD && AREM > 0) {
+        if (extra)
+          __builtin_amdgcn_global_load_lds((gptr_t)(asrc[NAQ] + ka * KS),
+                                           (lptr_t)(sta + (NAQ * 8 + wave) * 64), 16, 0, 0);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
-  }
+  };
+  const int spread_steps = ksteps - (SA - 1);
+  int ks = 0;
+  for (; ks < spread_steps; ++ks) turn(ks, std::true_type{});
+  for (; ks < ksteps; ++ks) turn(ks, std::false_type{});
+  if constexpr (NBW > 0) mfmas(1);                           // sub-step 3 of the last step
+#ifdef MOE_GEMM_TRACE
+  if (tr_tile) g_tile[blockIdx.x][2] = wall_clock64();
+#endif
 
+  // Epilogue.  Lane l holds column l%32 of each 32x32 block and rows
+  // (q/4)*8 + (l/32)*4 + q%4: two rows are rounded to bf16 by one packed convert
+  // and stored as the low / high half.  Only the last 32-row block of a tile can
+  // hold rows of the next expert's segment; the others are stored unpredicated.
   if constexpr (NBW > 0) {
+    const int lrow = arow + (lane >> 5) * 4;                    // first row of this lane, tile-relative
+    const int valid = row1 - row0 - lrow;                        // rows r (tile-relative to lrow) < valid exist
+    uint16_t* const cl = C + size_t(row0 + lrow) * N + n0 + (lane & 31);
+    auto put2 = [&](uint16_t* p, float v0, float v1, bool ok0, bool ok1) {
+      uint32_t pk;   // bf16(v0) | bf16(v1) << 16, round to nearest even
+      asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pk) : "v"(v0), "v"(v1));
+      if (ok0) p[0] = uint16_t(pk);
+      if (ok1) p[N] = uint16_t(pk >> 16);
+    };
+    auto store_block = [&](int i, auto pred_c) {
+      constexpr bool PRED = decltype(pred_c)::value;
 #pragma unroll
-    for (int i = 0; i < NBW; ++i) {
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int row = row0 + arow + i * 32 + (q >> 2) * 8 + (lane >> 5) * 4 + (q & 3);
-        if (row >= row1) continue;
+      for (int q = 0; q < 16; q += 2) {
+        const int r = i * 32 + (q >> 2) * 8 + (q & 3);
+        const bool ok0 = !PRED || r < valid, ok1 = !PRED || r + 1 < valid;
+        uint16_t* const p = cl + size_t(r) * N;
         if (DUAL) {
-          const int col = n0 + wn * 32 + (lane & 31);
-          if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(silu_mul(acc[i][0][q], acc[i][1][q]));
+          if (n0 + wn * 32 < N)
+            put2(p + wn * 32, silu_mul_fast(acc[i][0][q], acc[i][1][q]),
+                 silu_mul_fast(acc[i][0][q + 1], acc[i][1][q + 1]), ok0, ok1);
         } else {
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-            if (col < N) C[size_t(row) * N + col] = f32_to_bf16_bits(acc[i][j][q]);
-          }
+          for (int j = 0; j < 2; ++j)
+            if (n0 + wn * 64 + j * 32 < N)
+              put2(p + wn * 64 + j * 32, acc[i][j][q], acc[i][j][q + 1], ok0, ok1);
         }
       }
+    };
+    const bool full = row1 - row0 == NB * 32;
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+      if (i == NBW - 1 && WM * 4 + NBW == NB && !full) store_block(i, std::true_type{});
+      else store_block(i, std::false_type{});
     }
   }
+#ifdef MOE_GEMM_TRACE
+  if (tr_tile) g_tile[blockIdx.x][3] = wall_clock64();
+#endif
 }
 
 template <bool DUAL, int NB>
@@ -827,12 +962,15 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   const int H = c.hidden, I = c.inter_local;
   // Few rows per expert means the weights are streamed about once: cap the tile
   // height at 160 rows there, which leaves room for a three-stage ring.
-  const int bm = rows_capacity / n_experts <= 320 ? 160 : 256;
+  int bm = rows_capacity / n_experts <= 320 ? 160 : 256;
+#if defined(MOE_GEMM_TRACE) || defined(MOE_TUNE)
+  if (getenv("MOE_BM")) bm = atoi(getenv("MOE_BM"));
+#endif
   const int max_mt = rows_capacity / bm + n_experts;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, bm,
              rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 1);
   const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
-  constexpr int lds = 160 * 1024 - 4096;  // the ring of every tile height fits below this
+  constexpr int lds = 160 * 1024;         // all of a CU's LDS: the rings of the tallest tile fill it
   const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt * nt2 + 7) / 8 * 8;
   auto k1 = ffn_gemm8w_kernel<true>;
   auto k2 = ffn_gemm8w_kernel<false>;
@@ -899,3 +1037,12 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
 }
 
 }  // namespace moe
+
+#ifdef MOE_GEMM_TRACE
+extern "C" int moe_debug_tile_read(unsigned long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(moe::g_tile), sizeof(moe::g_tile));
+}
+extern "C" int moe_debug_trace_read(unsigned long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(moe::g_trace), sizeof(moe::g_trace));
+}
+#endif
