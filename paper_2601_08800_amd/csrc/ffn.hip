@@ -16,7 +16,6 @@
 // and u of the same element and the SwiGLU is applied in registers.
 // fp8 weights: e4m3 codes are widened to bf16 (exact) on the way into LDS; the
 // 128x128 block scale multiplies the fp32 partial sum of each 128-deep K block.
-#include <cstdlib>
 #include <type_traits>
 
 #include "moe_internal.h"
@@ -53,7 +52,7 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 // row, index of the expert's first tile, number of tiles of the expert).
 constexpr int kTileRec = 5;
 #ifndef MOE_SPREAD_SLOTS
-#define MOE_SPREAD_SLOTS 3
+#define MOE_SPREAD_SLOTS 4
 #endif
 #ifndef MOE_RING_EXTRA_A
 #define MOE_RING_EXTRA_A 2
@@ -344,13 +343,6 @@ __device__ __forceinline__ int swz2(int row, int piece) {
 // moves whole cache lines.  (A K step of 32 would allow four stages for the tall
 // tiles too, but its 64-byte row pieces halve the efficiency of the load path:
 // measured 8 % slower on the 256-row tiles.)
-#ifdef MOE_GEMM_TRACE
-__device__ unsigned long long g_trace[16][160][4];
-__device__ unsigned long long g_tile[8192][4];   // per workgroup: hw id, wall clock at entry / after K loop / at exit
-#define MOE_STAMP(i) do { if (tr_slot >= 0 && ks < 160) { g_trace[tr_slot][ks][i] = __builtin_readcyclecounter(); } } while (0)
-#else
-#define MOE_STAMP(i) do {} while (0)
-#endif
 template <int NB> struct Ring {
   static constexpr int kBK = 64;
   static constexpr int kPPR = kBK / 8;                              // 16-byte pieces per row
@@ -471,15 +463,6 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     if (g + SB - 1 >= 0 && g + SB - 1 < ksteps) issue_b(g + SB - 1);
     if (g + SA - 1 < ksteps) issue_a(g + SA - 1);
   }
-#ifdef MOE_GEMM_TRACE
-  const bool tr_tile = DUAL && wave == 0 && lane == 0 && blockIdx.x < 8192;
-  if (tr_tile) {
-    g_tile[blockIdx.x][0] = (unsigned long long)__builtin_amdgcn_s_getreg(63492) |
-                            ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32);
-    g_tile[blockIdx.x][1] = wall_clock64();
-  }
-  const int tr_slot = (DUAL && wave == 0 && lane == 0 && blockIdx.x % 64 == 8 && blockIdx.x / 64 < 16) ? int(blockIdx.x / 64) : -1;
-#endif
   // One load instruction of a step's issue group: ops 0..NBQ-1 are the weight row
   // groups, NBQ..NBQ+NAQ-1 the activation row groups (weights first: see above).
   constexpr int NOPS = NBQ + NAQ;
@@ -523,13 +506,10 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   constexpr int OPK = (NOPS + NSLOT - 1) / NSLOT;            // load instructions per slot
   auto turn = [&](int ks, auto spread_c) {
     constexpr bool SPREAD = decltype(spread_c)::value && NBW > 0;
-    MOE_STAMP(0);
     // step ks must have landed
     wait_step(ks + SA - 2 < ksteps);
-    MOE_STAMP(1);
     // a bare barrier (no fence): __syncthreads() would also drain the younger loads
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    MOE_STAMP(2);
     // every wavefront has read all of step ks-1, so its stages can be refilled
     const int kb = ks + SB - 1, ka = ks + SA - 1;
     uint4* const stb = ringB + (kb % SB) * BS;
@@ -588,9 +568,6 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   for (; ks < spread_steps; ++ks) turn(ks, std::true_type{});
   for (; ks < ksteps; ++ks) turn(ks, std::false_type{});
   if constexpr (NBW > 0) mfmas(1);                           // sub-step 3 of the last step
-#ifdef MOE_GEMM_TRACE
-  if (tr_tile) g_tile[blockIdx.x][2] = wall_clock64();
-#endif
 
   // Epilogue.  Lane l holds column l%32 of each 32x32 block and rows
   // (q/4)*8 + (l/32)*4 + q%4: two rows are rounded to bf16 by one packed convert
@@ -632,9 +609,6 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
       else store_block(i, std::false_type{});
     }
   }
-#ifdef MOE_GEMM_TRACE
-  if (tr_tile) g_tile[blockIdx.x][3] = wall_clock64();
-#endif
 }
 
 template <bool DUAL, int NB>
@@ -962,10 +936,7 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   const int H = c.hidden, I = c.inter_local;
   // Few rows per expert means the weights are streamed about once: cap the tile
   // height at 160 rows there, which leaves room for a three-stage ring.
-  int bm = rows_capacity / n_experts <= 320 ? 160 : 256;
-#if defined(MOE_GEMM_TRACE) || defined(MOE_TUNE)
-  if (getenv("MOE_BM")) bm = atoi(getenv("MOE_BM"));
-#endif
+  const int bm = rows_capacity / n_experts <= 320 ? 160 : 256;
   const int max_mt = rows_capacity / bm + n_experts;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, bm,
              rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 1);
@@ -1038,11 +1009,3 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
 
 }  // namespace moe
 
-#ifdef MOE_GEMM_TRACE
-extern "C" int moe_debug_tile_read(unsigned long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(moe::g_tile), sizeof(moe::g_tile));
-}
-extern "C" int moe_debug_trace_read(unsigned long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(moe::g_trace), sizeof(moe::g_trace));
-}
-#endif
