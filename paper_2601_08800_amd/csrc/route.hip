@@ -600,36 +600,38 @@ __global__ __launch_bounds__(256) void route_select_kernel(
 }
 
 // --------------------------------------------------------- stage 3: re-score
-// One workgroup per listed token.  Phase 1 (only when the group cut is in
-// doubt): the experts that may be among their group's largest get exact keys and
-// the groups are chosen in fp64.  Phase 2: with the groups fixed, the experts
-// whose key interval reaches the picks get exact keys and the top-k is taken in
-// fp64.  Experts outside those sets keep their fast keys: by construction they
-// cannot change either decision.
+// One wavefront per listed token (four independent tokens per workgroup, no
+// workgroup barrier).  Phase 1 (only when the group cut is in doubt): the
+// experts that may be among their group's largest get exact keys and the groups
+// are chosen in fp64.  Phase 2: with the groups fixed, the experts whose key
+// interval reaches the picks get exact keys and the top-k is taken in fp64.
+// Experts outside those sets keep their fast keys: by construction they cannot
+// change either decision.  A wavefront's candidate list and exact logits live
+// in its own slice of LDS; LDS operations of one wavefront execute in order.
 template <int EPL, bool BF16>
-__global__ __launch_bounds__(256) void route_recheck_kernel(
+__global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     SelCfg c, int H, const void* __restrict__ x, const void* __restrict__ gate_w,
     const float* __restrict__ logits_in, const float* __restrict__ logits,
     const float* __restrict__ logit_bias, const float* __restrict__ select_bias,
     const float* __restrict__ xnorm2, const float* __restrict__ wnorm2, int32_t* __restrict__ ids,
     float* __restrict__ w, const int32_t* __restrict__ counters,
     const int32_t* __restrict__ recheck) {
-  __shared__ int xlist[512];
-  __shared__ double zx[512];
-  __shared__ int n_x;
-  __shared__ double part[4][8];
+  __shared__ int xlist_all[4][EPL * 64];
+  __shared__ double zx_all[4][EPL * 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int* const xlist = xlist_all[wave];
+  double* const zx = zx_all[wave];
   const int n_list = counters[0];
   const size_t eb = BF16 ? 2 : 4;
 
-  // exact logits of the experts in xlist[0..n) -> zx[e]; all four wavefronts
-  // The whole workgroup works on every dot product (thread-strided 16-byte
-  // pieces, the token row is loaded once per batch of CB experts), so many loads
-  // are in flight; partial sums are combined in a fixed order.
-  constexpr int CB = 8;
+  // exact logits of the experts in xlist[0..n) -> zx[e].  The wavefront walks the
+  // token row once per batch of CB experts, lane-strided 16-byte pieces, four
+  // pieces per lane and expert in flight; the lane sums are combined by a fixed
+  // butterfly.
+  constexpr int CB = 4;
   auto exact_logits = [&](int t, int n) {
     if (logits_in) {
-      for (int q = threadIdx.x; q < n; q += 256) {
+      for (int q = lane; q < n; q += 64) {
         const int e = xlist[q];
         double z = (double)logits_in[size_t(t) * c.E + e];
         if (logit_bias) z += (double)logit_bias[e];
@@ -642,39 +644,47 @@ __global__ __launch_bounds__(256) void route_recheck_kernel(
     for (int q0 = 0; q0 < n; q0 += CB) {
       double acc[CB];
       const char* wrow[CB];
+      int ex[CB];
 #pragma unroll
       for (int i = 0; i < CB; ++i) {
         acc[i] = 0.0;
-        const int e = xlist[q0 + i < n ? q0 + i : n - 1];
-        wrow[i] = static_cast<const char*>(gate_w) + size_t(e) * H * eb;
+        ex[i] = xlist[q0 + i < n ? q0 + i : n - 1];
+        wrow[i] = static_cast<const char*>(gate_w) + size_t(ex[i]) * H * eb;
       }
-      for (int p = threadIdx.x; p < n16; p += 256) {
-        const uint4 a = *reinterpret_cast<const uint4*>(xrow + size_t(p) * 16);
+      // U pieces per lane and expert in flight (the tail pieces are clamped to the
+      // last one and masked out of the sum)
+      constexpr int U = 4;
+      for (int p0 = 0; p0 < n16; p0 += 64 * U) {
+        uint4 a[U], b[CB][U];
+        bool in[U];
 #pragma unroll
-        for (int i = 0; i < CB; ++i) {
-          if (q0 + i < n) {
-            const uint4 b = *reinterpret_cast<const uint4*>(wrow[i] + size_t(p) * 16);
-            acc[i] = piece_dot64<BF16>(a, b, acc[i]);
-          }
+        for (int u = 0; u < U; ++u) {
+          int p = p0 + u * 64 + lane;
+          in[u] = p < n16;
+          p = in[u] ? p : n16 - 1;
+          a[u] = *reinterpret_cast<const uint4*>(xrow + size_t(p) * 16);
+#pragma unroll
+          for (int i = 0; i < CB; ++i) b[i][u] = *reinterpret_cast<const uint4*>(wrow[i] + size_t(p) * 16);
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int i = 0; i < CB; ++i) {
+            const double d = piece_dot64<BF16>(a[u], b[i][u], 0.0);
+            acc[i] += in[u] ? d : 0.0;
+          }
       }
 #pragma unroll
       for (int i = 0; i < CB; ++i) {
-        const double sm = wave_sum(acc[i]);
-        if (lane == 0) part[wave][i] = sm;
+        double z = wave_sum(acc[i]);
+        if (q0 + i < n && lane == 0) {
+          if (logit_bias) z += (double)logit_bias[ex[i]];
+          zx[ex[i]] = z;
+        }
       }
-      __syncthreads();
-      if (threadIdx.x < CB && q0 + int(threadIdx.x) < n) {
-        const int e = xlist[q0 + threadIdx.x];
-        double z = ((part[0][threadIdx.x] + part[1][threadIdx.x]) + part[2][threadIdx.x]) +
-                   part[3][threadIdx.x];
-        if (logit_bias) z += (double)logit_bias[e];
-        zx[e] = z;
-      }
-      __syncthreads();
     }
   };
-  // wavefront 0: list the experts flagged in `want` that are not yet exact
+  // list the experts flagged in `want`; returns how many
   auto make_list = [&](uint32_t want) {
     int n = 0;
 #pragma unroll
@@ -684,18 +694,17 @@ __global__ __launch_bounds__(256) void route_recheck_kernel(
       if (in) xlist[n + __popcll(m & ((uint64_t(1) << lane) - 1))] = i * 64 + lane;
       n += __popcll(m);
     }
-    if (lane == 0) n_x = n;
+    return n;
   };
 
-  for (int li = blockIdx.x; li < n_list; li += gridDim.x) {
+  for (int li = blockIdx.x * 4 + wave; li < n_list; li += gridDim.x * 4) {
     const int t = recheck[li];
     Keys<float, EPL> K;
     Keys<double, EPL> D;
     Groups<float> Gf;
     Gf.kept = 0; Gf.certain = true; Gf.need = 0;
     uint32_t exact = 0;          // slots of this lane that hold exact keys
-    uint64_t kept = 0;
-    auto adopt = [&](uint32_t want) {   // wavefront 0: pull exact logits into D
+    auto adopt = [&](uint32_t want) {   // pull exact logits into D
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
         if (!(want >> i & 1)) continue;
@@ -711,55 +720,40 @@ __global__ __launch_bounds__(256) void route_recheck_kernel(
       }
       exact |= want;
     };
-    if (wave == 0) {
-      const float xn = token_norm(c, xnorm2, t);
-      fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
+    const float xn = token_norm(c, xnorm2, t);
+    fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        D.key[i] = (double)K.key[i]; D.sc[i] = (double)K.sc[i]; D.eps[i] = 0.0;
-      }
-      if (c.G > 1) group_stage<float, EPL>(c, K, lane, Gf);
-      kept = Gf.kept;
-      make_list((c.G > 1 && !Gf.certain) ? Gf.need : 0u);
+    for (int i = 0; i < EPL; ++i) {
+      D.key[i] = (double)K.key[i]; D.sc[i] = (double)K.sc[i]; D.eps[i] = 0.0;
     }
-    __syncthreads();
-    int n = n_x;
-    if (n > 0) {                        // phase 1: settle the groups in fp64
+    if (c.G > 1) group_stage<float, EPL>(c, K, lane, Gf);
+    uint64_t kept = Gf.kept;
+    if (c.G > 1 && !Gf.certain) {       // phase 1: settle the groups in fp64
+      const int n = make_list(Gf.need);
       exact_logits(t, n);
-      __syncthreads();
-      if (wave == 0) {
-        adopt(Gf.need);
-        Groups<double> Gd;
-        group_stage<double, EPL>(c, D, lane, Gd);
-        kept = Gd.kept;
-      }
+      adopt(Gf.need);
+      Groups<double> Gd;
+      group_stage<double, EPL>(c, D, lane, Gd);
+      kept = Gd.kept;
     }
-    __syncthreads();
-    uint32_t elig = 0, want = 0;
-    if (wave == 0) {                    // phase 2: candidates of the top-k
-      elig = eligible_mask<EPL>(c, kept, lane);
-      Picks<float> P;
-      topk_stage<float, EPL>(c, K, elig, lane, P);
+    // phase 2: candidates of the top-k
+    const uint32_t elig = eligible_mask<EPL>(c, kept, lane);
+    Picks<float> P;
+    topk_stage<float, EPL>(c, K, elig, lane, P);
+    uint32_t want = 0;
 #pragma unroll
-      for (int i = 0; i < EPL; ++i)
-        if ((elig >> i & 1) && !(exact >> i & 1) && (K.key[i] + K.eps[i] >= P.low)) want |= 1u << i;
-      make_list(want);
-    }
-    __syncthreads();
-    n = n_x;
+    for (int i = 0; i < EPL; ++i)
+      if ((elig >> i & 1) && !(exact >> i & 1) && (K.key[i] + K.eps[i] >= P.low)) want |= 1u << i;
+    const int n = make_list(want);
     exact_logits(t, n);
-    __syncthreads();
-    if (wave == 0) {
-      adopt(want);
-      Picks<double> Q;
-      topk_stage<double, EPL>(c, D, elig, lane, Q);
-      const double wt = pick_weight<double, EPL>(c, D, Q, lane);
-      if (lane < c.k) {
-        ids[size_t(t) * c.k + lane] = Q.id;
-        w[size_t(t) * c.k + lane] = (float)wt;
-      }
+    adopt(want);
+    Picks<double> Q;
+    topk_stage<double, EPL>(c, D, elig, lane, Q);
+    const double wt = pick_weight<double, EPL>(c, D, Q, lane);
+    if (lane < c.k) {
+      ids[size_t(t) * c.k + lane] = Q.id;
+      w[size_t(t) * c.k + lane] = (float)wt;
     }
-    __syncthreads();
   }
 }
 
@@ -772,7 +766,7 @@ void launch_select_and_recheck(const SelCfg& sc, const moe_config& c, int T, con
   MOE_LAUNCH(MOE_K_SELECT, route_select_kernel<EPL>, dim3((T + 3) / 4), dim3(256), 0, s, sc, T, logits,
                      logit_bias, select_bias, ws.xnorm2, ws.wnorm2, ids, w, ws.counters,
                      ws.recheck);
-  const int grid = T < 4096 ? T : 4096;
+  const int grid = T < 4096 ? (T + 3) / 4 : 1024;   // four tokens per workgroup at a time
   if (c.act_dtype == MOE_BF16)
     MOE_LAUNCH(MOE_K_RESCORE, (route_recheck_kernel<EPL, true>), dim3(grid), dim3(256), 0, s, sc,
                        c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
