@@ -190,11 +190,58 @@ def main():
         "stages": stages,
     }
 
+    out["next_rows"] = next_rows(moe, L, w, x, a_loc, tokens_local, max(args.steps, 5))
+
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x_np, gate, experts, shared, forced_np,
                                            args.cpu_seconds)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def next_rows(moe, L, w, x, a_loc, tokens_local, steps):
+    """The collective-ready layouts of the fused schedules, measured on their
+    own (they are not part of the timed step): the hidden-column shard dispatch
+    of one TP rank, and one stage of the staged combine on one column block,
+    overwriting and accumulating.  Kernel durations from HIP events; GB/s on
+    the algorithmic bytes of the shard / block."""
+    import torch
+    cfg = L.cfg
+    m = w.tp if w.tp > 1 else 8                    # ranks of the intra-node TP group
+    if w.H % m or (w.H // m) % 8:
+        return None
+    ab = 4 if w.act_dtype == "f32" else 2
+    T, k, Hs = w.T, w.k, w.H // m
+    A = T * k
+    xs_shard = torch.empty((A, Hs), dtype=L.xs.dtype, device=L.xs.device)
+    ys_block = torch.empty((max(a_loc, 1), Hs), dtype=L.ys.dtype, device=L.ys.device).normal_()
+    out_block = torch.zeros((T, Hs), dtype=torch.float32, device=L.ys.device)
+    res = {"tp_size": m, "shard_columns": Hs}
+
+    def timed(fn, kernel):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        moe.moe_profile_enable(16 * steps)
+        moe.moe_profile_filter([kernel])
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        ms = moe.moe_profile_read()[kernel][0]
+        moe.moe_profile_filter(None)
+        moe.moe_profile_enable(0)
+        return ms * 1e3 / steps
+
+    us = timed(lambda: moe.moe_dispatch_shard(cfg, T, x, L.topk_ids, 0, m, L.counts, L.offsets,
+                                              L.perm, L.inv, xs_shard, L.ws), "dispatch_gather")
+    by = tokens_local * Hs * ab + a_loc * Hs * ab + A * 4
+    res["dispatch_shard_gather"] = {"us": round(us, 2), "GBps": round(by / us / 1e3, 1)}
+    for acc, name in ((0, "combine_stage"), (1, "combine_stage_accumulate")):
+        us = timed(lambda: moe.moe_combine_stage(cfg, T, ys_block, L.inv, L.topk_w, m, acc,
+                                                 out_block), "combine")
+        by = a_loc * Hs * ab + A * 8 + T * Hs * 4 * (2 if acc else 1)
+        res[name] = {"us": round(us, 2), "GBps": round(by / us / 1e3, 1)}
+    return res
 
 
 def cpu_baseline(w, x_np, gate, experts, shared, forced_np, budget_s):

@@ -127,6 +127,23 @@ moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
                         void* stream);
 
 /*
+ * Dispatch for the fused AG-Dispatch schedule (Alg. 2; Sec. III-C-2: hidden
+ * states are replicated inside the MoE TP group, so they can be sharded there).
+ * TP rank `tp_rank` of `tp_size` computes the expert map as moe_dispatch does
+ * and builds the send buffer from its own hidden-column shard X_{r_TP} only;
+ * the all-gather on the receiving node completes the rows.  counts / offsets /
+ * perm / inv are those of moe_dispatch;
+ *   xs_shard out [T*k, H/tp_size] act dtype:
+ *     xs_shard[pos, c] = x[perm[pos]/k, tp_rank*H/tp_size + c]
+ * H must be a multiple of tp_size and H/tp_size a multiple of 8.  tp_rank 0 of
+ * 1 is moe_dispatch.
+ */
+moe_status moe_dispatch_shard(const moe_config* cfg, int32_t T, const void* x,
+                              const int32_t* topk_ids, int32_t tp_rank, int32_t tp_size,
+                              int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
+                              void* xs_shard, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Grouped expert MLP (Sec. II: each expert is an independent MLP; under TP the
  * projections are sliced and the partial results are summed afterwards).  For
  * expert e in [0, n_experts_here) and every row r in [offsets[e], offsets[e+1]):
@@ -158,6 +175,24 @@ moe_status moe_expert_ffn(const moe_config* cfg, int32_t n_experts_here, const v
  */
 moe_status moe_combine(const moe_config* cfg, int32_t T, const void* ys, const int32_t* inv,
                        const float* topk_w, const void* shared_ys, float* out, void* stream);
+
+/*
+ * One stage of the fused RS-Combine schedule (Alg. 1): the hidden dimension is
+ * split into tp_size blocks; stage i hands this rank S_i, the reduce-scattered
+ * expert outputs that one source node returned, restricted to the rank's block,
+ * and the stage result is accumulated: Y_block <- Y_block + topk_weights(S_i).
+ *   ys_block  [>= rows, H/tp_size] act dtype (rows addressed through inv)
+ *   inv [T*k], topk_w [T,k]: as in moe_combine, for the assignments of this stage
+ *   out_block [T, H/tp_size] fp32:
+ *     s[t,c] = sum_{j : inv[t*k+j] >= 0} topk_w[t,j] * ys_block[inv[t*k+j], c]
+ *              (ascending j, fp32)
+ *     accumulate == 0: out_block = s (first stage; out_block need not be
+ *     initialised); accumulate == 1: out_block = out_block + s
+ * tp_size 1 with accumulate 0 is moe_combine without a shared expert.
+ */
+moe_status moe_combine_stage(const moe_config* cfg, int32_t T, const void* ys_block,
+                             const int32_t* inv, const float* topk_w, int32_t tp_size,
+                             int32_t accumulate, float* out_block, void* stream);
 
 /*
  * Per-kernel timing for benchmarks (not part of the layer; Sec. III-A calls for

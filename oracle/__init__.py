@@ -165,6 +165,44 @@ def combine(ys, inv, w, shared_ys=None):
     return out
 
 
+def dispatch_shard(ids, x, e_lo, e_hi, tp_rank, tp_size):
+    """Send buffer of TP rank `tp_rank` of `tp_size` in the fused AG-Dispatch
+    schedule: the rank's hidden-column shard of every routed row.  Returns
+    counts, offsets, perm, inv, xs_shard float32 [A_loc, H/tp_size]."""
+    ids = np.ascontiguousarray(ids, np.int32)
+    T, k = ids.shape
+    xf = decode(x)
+    H = xf.shape[1]
+    assert H % tp_size == 0 and 0 <= tp_rank < tp_size
+    E_loc = e_hi - e_lo
+    counts = np.empty((E_loc,), np.int32)
+    offsets = np.empty((E_loc + 1,), np.int32)
+    perm = np.full((T * k,), -1, np.int32)
+    inv = np.empty((T * k,), np.int32)
+    xs = np.zeros((T * k, H // tp_size), np.float32)
+    _load().oracle_dispatch_shard(T, k, H, e_lo, e_hi, tp_rank, tp_size, _p(ids), _p(xf),
+                                  _p(counts), _p(offsets), _p(perm), _p(inv), _p(xs))
+    n = int(offsets[-1])
+    return counts, offsets, perm[:n].copy(), inv, xs[:n].copy()
+
+
+def combine_stage(ys_block, inv, w, out_block=None):
+    """One stage of the fused RS-Combine on one hidden-column block:
+    out_block (+)= gate-weighted rows of ys_block.  `out_block` None starts a
+    new block (accumulate = 0); otherwise it is added to.  Returns float32."""
+    ys_block = np.ascontiguousarray(ys_block, np.float64)
+    w = np.ascontiguousarray(w, np.float32)
+    T, k = w.shape
+    Hb = ys_block.shape[1]
+    if ys_block.shape[0] == 0:
+        ys_block = np.zeros((1, Hb), np.float64)
+    inv = np.ascontiguousarray(inv, np.int32).reshape(T * k)
+    acc = 0 if out_block is None else 1
+    out = np.empty((T, Hb), np.float32) if out_block is None else np.array(out_block, np.float32, order="C")
+    _load().oracle_combine_stage(T, k, Hb, _p(ys_block), _p(inv), _p(w), acc, _p(out))
+    return out
+
+
 def layer_share(x, ids, w, e_lo, e_hi, experts, shared=None):
     """dispatch -> expert MLP -> (shared expert) -> combine for given routing.
     `experts` / `shared` are dicts with w_gate,w_up,w_down,s_gate,s_up,s_down.

@@ -266,6 +266,65 @@ void oracle_combine(int T, int k, int H, const double *ys, const int32_t *inv,
     }
 }
 
+/* ---- collective-ready layouts of the fused schedules (Sec. III-C, Alg. 1, 2) ---- */
+/*
+ * Fused AG-Dispatch (Alg. 2): hidden states are replicated in the TP group, so
+ * TP rank r of m computes the expert map on its own and sends only its hidden-
+ * column shard X_r of every routed row.  Index outputs as oracle_dispatch;
+ *   xs_shard [A_loc, H/m]:  xs_shard[pos][c] = x[perm[pos]/k][r*H/m + c].
+ */
+void oracle_dispatch_shard(int T, int k, int H, int e_lo, int e_hi, int tp_rank, int tp_size,
+                           const int32_t *ids, const float *x,
+                           int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv,
+                           float *xs_shard)
+{
+    int E_loc = e_hi - e_lo;
+    int A = T * k;
+    int Hs = H / tp_size;
+    for (int e = 0; e < E_loc; ++e) counts[e] = 0;
+    for (int a = 0; a < A; ++a)
+        if (ids[a] >= e_lo && ids[a] < e_hi) counts[ids[a] - e_lo]++;
+    offsets[0] = 0;
+    for (int e = 0; e < E_loc; ++e) offsets[e + 1] = offsets[e] + counts[e];
+    int32_t *fill = (int32_t *)calloc(E_loc > 0 ? E_loc : 1, sizeof(int32_t));
+    for (int a = 0; a < A; ++a) {
+        int e = ids[a] - e_lo;
+        if (e >= 0 && e < E_loc) {
+            int pos = offsets[e] + fill[e]++;
+            perm[pos] = a;
+            inv[a] = pos;
+            for (int c = 0; c < Hs; ++c)
+                xs_shard[(size_t)pos * Hs + c] = x[(size_t)(a / k) * H + (size_t)tp_rank * Hs + c];
+        } else {
+            inv[a] = -1;
+        }
+    }
+    free(fill);
+}
+
+/*
+ * One stage of the fused RS-Combine (Alg. 1): Y_i <- Y_i + topk_weights(S_i),
+ * on one hidden-column block of width Hb = H/m.
+ *   s[t][c] = sum_{j: inv[t*k+j] >= 0} w[t][j] * ys_block[inv[t*k+j]][c]   (fp64)
+ *   out_block[t][c] = (accumulate ? out_block[t][c] : 0) + s[t][c], stored fp32.
+ */
+void oracle_combine_stage(int T, int k, int Hb, const double *ys_block, const int32_t *inv,
+                          const float *w, int accumulate, float *out_block)
+{
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        for (int c = 0; c < Hb; ++c) {
+            double acc = 0.0;
+            for (int j = 0; j < k; ++j) {
+                int pos = inv[(size_t)t * k + j];
+                if (pos >= 0) acc += (double)w[(size_t)t * k + j] * ys_block[(size_t)pos * Hb + c];
+            }
+            if (accumulate) acc += (double)out_block[(size_t)t * Hb + c];
+            out_block[(size_t)t * Hb + c] = (float)acc;
+        }
+    }
+}
+
 /* ---- storage decoders (exact) ------------------------------------------- */
 /* OCP e4m3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; exponent field 0 is
  * subnormal (m/8 * 2^-6); 0x7F / 0xFF are NaN; there are no infinities. */

@@ -14,7 +14,8 @@ _LIB_PATH = os.path.join(_PKG, "libmoe.so")
 _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatch",
-           "moe_expert_ffn", "moe_combine", "moe_profile_enable", "moe_profile_read",
+           "moe_dispatch_shard", "moe_expert_ffn", "moe_combine", "moe_combine_stage",
+           "moe_profile_enable", "moe_profile_read",
            "moe_profile_filter",
            "moe_kernel_name")
 MOE_K_COUNT = 12
@@ -64,6 +65,10 @@ def load_library():
         lib.moe_route.argtypes = [cfgp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_dispatch.restype = ctypes.c_int
         lib.moe_dispatch.argtypes = [cfgp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_dispatch_shard.restype = ctypes.c_int
+        lib.moe_dispatch_shard.argtypes = [cfgp, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_combine_stage.restype = ctypes.c_int
+        lib.moe_combine_stage.argtypes = [cfgp, i32, vp, vp, vp, i32, i32, vp, vp]
         lib.moe_expert_ffn.restype = ctypes.c_int
         lib.moe_expert_ffn.argtypes = [cfgp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_combine.restype = ctypes.c_int
@@ -133,6 +138,16 @@ def moe_dispatch(cfg, T, x, topk_ids, counts, offsets, perm, inv, xs, ws, stream
     _check(st, "moe_dispatch")
 
 
+def moe_dispatch_shard(cfg, T, x, topk_ids, tp_rank, tp_size, counts, offsets, perm, inv, xs_shard,
+                       ws, stream=None, ws_bytes=None):
+    st = load_library().moe_dispatch_shard(ctypes.byref(cfg), T, _ptr(x), _ptr(topk_ids), tp_rank,
+                                           tp_size, _ptr(counts), _ptr(offsets), _ptr(perm),
+                                           _ptr(inv), _ptr(xs_shard), _ptr(ws),
+                                           _ws_bytes(ws) if ws_bytes is None else ws_bytes,
+                                           _stream(stream))
+    _check(st, "moe_dispatch_shard")
+
+
 def moe_expert_ffn(cfg, n_experts_here, xs, offsets, rows_capacity, w_gate, w_up, w_down,
                    s_gate, s_up, s_down, ys, ws, stream=None, ws_bytes=None):
     st = load_library().moe_expert_ffn(ctypes.byref(cfg), n_experts_here, _ptr(xs), _ptr(offsets),
@@ -147,6 +162,13 @@ def moe_combine(cfg, T, ys, inv, topk_w, shared_ys, out, stream=None):
     st = load_library().moe_combine(ctypes.byref(cfg), T, _ptr(ys), _ptr(inv), _ptr(topk_w),
                                     _ptr(shared_ys), _ptr(out), _stream(stream))
     _check(st, "moe_combine")
+
+
+def moe_combine_stage(cfg, T, ys_block, inv, topk_w, tp_size, accumulate, out_block, stream=None):
+    st = load_library().moe_combine_stage(ctypes.byref(cfg), T, _ptr(ys_block), _ptr(inv),
+                                          _ptr(topk_w), tp_size, int(accumulate), _ptr(out_block),
+                                          _stream(stream))
+    _check(st, "moe_combine_stage")
 
 
 def moe_profile_enable(max_records: int):

@@ -40,7 +40,8 @@ __device__ __forceinline__ void fma8(float (&acc)[8], float w, const uint4& v) {
 // bf16 rows: a piece is 8 elements (16 B in, 32 B out).
 __global__ __launch_bounds__(256) void combine_bf16_kernel(
     const uint4* __restrict__ ys, const int32_t* __restrict__ inv, const float* __restrict__ w,
-    const uint4* __restrict__ shared_ys, float4* __restrict__ out, int T, int k, int row8) {
+    const uint4* __restrict__ shared_ys, float4* __restrict__ out, int T, int k, int row8,
+    int accumulate) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -88,6 +89,11 @@ __global__ __launch_bounds__(256) void combine_bf16_kernel(
       const int c = c0 + 64 * i;
       if (c < row8) {
         float4* o = out + (size_t(t) * row8 + c) * 2;
+        if (accumulate) {                     // Y <- Y + (weighted sum of this stage)
+          const float4 o0 = o[0], o1 = o[1];
+          acc[i][0] += o0.x; acc[i][1] += o0.y; acc[i][2] += o0.z; acc[i][3] += o0.w;
+          acc[i][4] += o1.x; acc[i][5] += o1.y; acc[i][6] += o1.z; acc[i][7] += o1.w;
+        }
         nt_store16(o, make_uint4(__float_as_uint(acc[i][0]), __float_as_uint(acc[i][1]),
                                  __float_as_uint(acc[i][2]), __float_as_uint(acc[i][3])));
         nt_store16(o + 1, make_uint4(__float_as_uint(acc[i][4]), __float_as_uint(acc[i][5]),
@@ -100,7 +106,8 @@ __global__ __launch_bounds__(256) void combine_bf16_kernel(
 // fp32 rows: a piece is 4 elements.
 __global__ __launch_bounds__(256) void combine_f32_kernel(
     const float4* __restrict__ ys, const int32_t* __restrict__ inv, const float* __restrict__ w,
-    const float4* __restrict__ shared_ys, float4* __restrict__ out, int T, int k, int row4) {
+    const float4* __restrict__ shared_ys, float4* __restrict__ out, int T, int k, int row4,
+    int accumulate) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -129,23 +136,30 @@ __global__ __launch_bounds__(256) void combine_f32_kernel(
       const float4 v = shared_ys[size_t(t) * row4 + c];
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
+    if (accumulate) {
+      const float4 o = out[size_t(t) * row4 + c];
+      acc.x += o.x; acc.y += o.y; acc.z += o.z; acc.w += o.w;
+    }
     out[size_t(t) * row4 + c] = acc;
   }
 }
 
 }  // namespace
 
+// `width` = elements per row of ys / shared_ys / out (the hidden size, or one
+// hidden-column block of it).
 hipError_t launch_combine(const moe_config& c, int T, const void* ys, const int32_t* inv,
-                          const float* w, const void* shared_ys, float* out, hipStream_t s) {
+                          const float* w, const void* shared_ys, float* out, int width,
+                          int accumulate, hipStream_t s) {
   const dim3 grid((T + 3) / 4), block(256);
   if (c.act_dtype == MOE_BF16) {
     MOE_LAUNCH(MOE_K_COMBINE, combine_bf16_kernel, grid, block, 0, s, static_cast<const uint4*>(ys), inv,
                        w, static_cast<const uint4*>(shared_ys), reinterpret_cast<float4*>(out), T,
-                       c.top_k, c.hidden / 8);
+                       c.top_k, width / 8, accumulate);
   } else {
     MOE_LAUNCH(MOE_K_COMBINE, combine_f32_kernel, grid, block, 0, s, static_cast<const float4*>(ys), inv,
                        w, static_cast<const float4*>(shared_ys), reinterpret_cast<float4*>(out), T,
-                       c.top_k, c.hidden / 4);
+                       c.top_k, width / 4, accumulate);
   }
   return hipGetLastError();
 }

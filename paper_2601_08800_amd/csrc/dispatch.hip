@@ -138,12 +138,14 @@ __global__ __launch_bounds__(64) void dispatch_scan_kernel(int32_t* __restrict__
 }
 
 // One wavefront per token: read the row once, write it to every local position.
-// `row16` = row length in 16-byte pieces.
+// Lengths in 16-byte pieces: `src16` = pitch of a token row, `col16` = first
+// piece of the copied column window, `row16` = width of the window = pitch of
+// the destination rows (the whole row: col16 = 0, row16 = src16).
 template <int PIECES>
 __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __restrict__ x,
                                                              const int32_t* __restrict__ inv,
                                                              uint4* __restrict__ xs, int T, int k,
-                                                             int row16) {
+                                                             int src16, int col16, int row16) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __res
   if (lane < k) pos = inv[size_t(t) * k + lane];      // k <= 32
   const uint64_t have = __ballot(pos >= 0);
   if (!have) return;
-  const uint4* src = x + size_t(t) * row16;
+  const uint4* src = x + size_t(t) * src16 + col16;
   for (int c0 = 0; c0 < row16; c0 += 64 * PIECES) {
     uint4 v[PIECES];
 #pragma unroll
@@ -178,7 +180,8 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __res
 
 hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int32_t* ids,
                            int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
-                           void* xs, const DispatchWs& ws, hipStream_t s) {
+                           void* xs, int tp_rank, int tp_size, const DispatchWs& ws,
+                           hipStream_t s) {
   const int k = c.top_k;
   const int A = T * k;
   const int E_loc = c.expert_hi - c.expert_lo;
@@ -190,9 +193,12 @@ hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int3
              n_sub, counts);
   MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_place_kernel, dim3((A + 255) / 256), block_idx, 0, s,
              ids, A, c.expert_lo, E_loc, n_sub, ws.block_hist, counts, offsets, perm, inv);
-  const int row16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
+  // column window of TP rank tp_rank of tp_size (the whole row for 0 of 1)
+  const int src16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
+  const int row16 = src16 / tp_size;
   MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_gather_kernel<8>, dim3((T + 3) / 4), dim3(256), 0, s,
-                     static_cast<const uint4*>(x), inv, static_cast<uint4*>(xs), T, k, row16);
+             static_cast<const uint4*>(x), inv, static_cast<uint4*>(xs), T, k, src16,
+             tp_rank * row16, row16);
   return hipGetLastError();
 }
 

@@ -123,13 +123,21 @@ moe_status moe_route(const moe_config* cfg, int32_t T, const void* x, const void
   return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
 }
 
-moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
-                        const int32_t* topk_ids, int32_t* counts, int32_t* offsets,
-                        int32_t* perm, int32_t* inv, void* xs, void* ws, size_t ws_bytes,
-                        void* stream) {
+namespace {
+// hidden-column sharding over a TP group: the shard must be whole 16-byte pieces
+bool shard_ok(const moe_config* cfg, int32_t tp_rank, int32_t tp_size) {
+  if (tp_size < 1 || tp_rank < 0 || tp_rank >= tp_size) return false;
+  if (cfg->hidden % tp_size) return false;
+  return (cfg->hidden / tp_size) % 8 == 0;
+}
+
+moe_status dispatch_impl(const moe_config* cfg, int32_t T, const void* x, const int32_t* topk_ids,
+                         int32_t tp_rank, int32_t tp_size, int32_t* counts, int32_t* offsets,
+                         int32_t* perm, int32_t* inv, void* xs, void* ws, size_t ws_bytes,
+                         void* stream) {
   moe_status st = check_config(cfg);
   if (st != MOE_OK) return st;
-  if (T < 0) return MOE_ERR_INVALID_ARG;
+  if (T < 0 || !shard_ok(cfg, tp_rank, tp_size)) return MOE_ERR_INVALID_ARG;
   if (T == 0) return MOE_OK;
   if (size_t(T) * cfg->top_k > (size_t(1) << 30)) return MOE_ERR_UNSUPPORTED;
   if (!x || !topk_ids || !counts || !offsets || !perm || !inv || !xs || !ws)
@@ -139,9 +147,26 @@ moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
     if (!aligned16(p)) return MOE_ERR_INVALID_ARG;
   DispatchWs d = carve_dispatch(ws, T, cfg->top_k, cfg->expert_hi - cfg->expert_lo);
   if (ws_bytes < d.bytes) return MOE_ERR_WORKSPACE;
-  hipError_t e = launch_dispatch(*cfg, T, x, topk_ids, counts, offsets, perm, inv, xs, d,
-                                 static_cast<hipStream_t>(stream));
+  hipError_t e = launch_dispatch(*cfg, T, x, topk_ids, counts, offsets, perm, inv, xs, tp_rank,
+                                 tp_size, d, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
+}
+}  // namespace
+
+moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
+                        const int32_t* topk_ids, int32_t* counts, int32_t* offsets,
+                        int32_t* perm, int32_t* inv, void* xs, void* ws, size_t ws_bytes,
+                        void* stream) {
+  return dispatch_impl(cfg, T, x, topk_ids, 0, 1, counts, offsets, perm, inv, xs, ws, ws_bytes,
+                       stream);
+}
+
+moe_status moe_dispatch_shard(const moe_config* cfg, int32_t T, const void* x,
+                              const int32_t* topk_ids, int32_t tp_rank, int32_t tp_size,
+                              int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
+                              void* xs_shard, void* ws, size_t ws_bytes, void* stream) {
+  return dispatch_impl(cfg, T, x, topk_ids, tp_rank, tp_size, counts, offsets, perm, inv, xs_shard,
+                       ws, ws_bytes, stream);
 }
 
 moe_status moe_expert_ffn(const moe_config* cfg, int32_t n_experts_here, const void* xs,
@@ -179,7 +204,25 @@ moe_status moe_combine(const moe_config* cfg, int32_t T, const void* ys, const i
   const void* ptrs[] = {ys, inv, topk_w, shared_ys, out};
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return MOE_ERR_INVALID_ARG;
-  hipError_t e = launch_combine(*cfg, T, ys, inv, topk_w, shared_ys, out,
+  hipError_t e = launch_combine(*cfg, T, ys, inv, topk_w, shared_ys, out, cfg->hidden, 0,
+                                static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
+}
+
+moe_status moe_combine_stage(const moe_config* cfg, int32_t T, const void* ys_block,
+                             const int32_t* inv, const float* topk_w, int32_t tp_size,
+                             int32_t accumulate, float* out_block, void* stream) {
+  moe_status st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (T < 0 || !shard_ok(cfg, 0, tp_size) || (accumulate != 0 && accumulate != 1))
+    return MOE_ERR_INVALID_ARG;
+  if (T == 0) return MOE_OK;
+  if (!ys_block || !inv || !topk_w || !out_block) return MOE_ERR_INVALID_ARG;
+  const void* ptrs[] = {ys_block, inv, topk_w, out_block};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return MOE_ERR_INVALID_ARG;
+  hipError_t e = launch_combine(*cfg, T, ys_block, inv, topk_w, nullptr, out_block,
+                                cfg->hidden / tp_size, accumulate,
                                 static_cast<hipStream_t>(stream));
   return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
 }

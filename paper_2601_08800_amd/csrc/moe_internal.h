@@ -70,7 +70,8 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
 
 hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int32_t* ids,
                            int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
-                           void* xs, const DispatchWs& ws, hipStream_t s);
+                           void* xs, int tp_rank, int tp_size, const DispatchWs& ws,
+                           hipStream_t s);
 
 hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
                              const int32_t* offsets, int rows_capacity, const void* w_gate,
@@ -79,6 +80,7 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
                              const FfnWs& ws, hipStream_t s);
 
 hipError_t launch_combine(const moe_config& c, int T, const void* ys, const int32_t* inv,
-                          const float* w, const void* shared_ys, float* out, hipStream_t s);
+                          const float* w, const void* shared_ys, float* out, int width,
+                          int accumulate, hipStream_t s);
 
 }  // namespace moe

@@ -97,3 +97,15 @@ def test_pointer_and_size_checks():
     assert status_of(moe.moe_expert_ffn, c, 8, None, None, 0, None, None, None, None, None, None, None, None, None, 0) == B.MOE_OK
     assert status_of(moe.moe_combine, c, 0, None, None, None, None, None) == B.MOE_OK
     assert moe.moe_status_string(B.MOE_ERR_WORKSPACE) == "workspace too small"
+
+
+def test_shard_arguments_are_validated():
+    c = cfg()
+    args = lambda r, m: (c, 8, P, P, r, m, P, P, P, P, P, P, None, 1 << 30)
+    bad = [(-1, 2), (2, 2), (0, 0), (0, 3), (0, 64)]     # rank out of range; H=256 not divisible / shard not whole pieces
+    for r, m in bad:
+        assert status_of(moe.moe_dispatch_shard, *args(r, m)) == B.MOE_ERR_INVALID_ARG
+    assert status_of(moe.moe_combine_stage, c, 8, P, P, P, 3, 0, P) == B.MOE_ERR_INVALID_ARG
+    assert status_of(moe.moe_combine_stage, c, 8, P, P, P, 2, 2, P) == B.MOE_ERR_INVALID_ARG
+    assert status_of(moe.moe_combine_stage, c, 8, None, P, P, 2, 0, P) == B.MOE_ERR_INVALID_ARG
+    assert status_of(moe.moe_combine_stage, c, 0, None, None, None, 2, 0, None) == B.MOE_OK

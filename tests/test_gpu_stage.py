@@ -1,0 +1,146 @@
+"""Collective-ready layouts on the GPU against the oracle, through the C ABI:
+the hidden-column shard dispatch of the fused AG-Dispatch (Alg. 2) and the
+per-stage accumulation of the fused RS-Combine (Alg. 1).  Integer outputs and
+copied rows are bit-exact; the fp32 block sums are compared to the oracle's
+fp64 sums with the fp32 bar (each stage stores fp32, at most k fused
+multiply-adds per element and stage)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2601_08800_amd as moe
+from paper_2601_08800_amd.layer import config_from_workload
+from workloads import gen
+from helpers import dev, host, inputs, oracle_route
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # fp32 activations, two ranks
+    "c1_tp2": (gen.CONFIGS["c1"], 2, 2),
+    # ragged token count, EP sub-range, four ranks, two source nodes
+    "ep_tp4": (gen.CONFIGS["c3"].replace(name="ep_tp4", T=333, H=256, E=64, k=8, I=64,
+                                         expert_lo=8, expert_hi=24), 4, 2),
+    # sigmoid / grouped routing, eight ranks (32-column shards), four source nodes
+    "ds_tp8": (gen.CONFIGS["c4"].replace(name="ds_tp8", T=257, H=512, E=64, k=8, I=64,
+                                         expert_lo=0, expert_hi=32, shared_expert=False), 8, 4),
+    # one rank: must reproduce the plain entry points
+    "one_rank": (gen.CONFIGS["c2p"].replace(name="one_rank", T=100, H=128, E=16, k=4, I=64), 1, 1),
+}
+
+
+def bf16_bits(a32):
+    return gen.f32_to_bf16_bits(np.ascontiguousarray(a32, np.float32))
+
+
+def run_case(w, m, n_nodes, ids, topk_w, ranks, sample_rows=None):
+    """ids / topk_w: numpy routing.  Checks every rank in `ranks`."""
+    cfg = config_from_workload(w)
+    d = inputs(w)
+    x_np = d["x"]
+    x = dev(x_np)
+    T, k, H = w.T, w.k, w.H
+    A = T * k
+    El = w.e_hi - w.expert_lo
+    Hs = H // m
+    adt = torch.float32 if w.act_dtype == "f32" else torch.bfloat16
+    i32 = dict(dtype=torch.int32, device="cuda")
+    counts, offsets = torch.empty(El, **i32), torch.empty(El + 1, **i32)
+    perm, inv = torch.empty(A, **i32), torch.empty(A, **i32)
+    ws = torch.empty(max(moe.moe_workspace_bytes(cfg, T), 256), dtype=torch.uint8, device="cuda")
+    ids_d, w_d = dev(ids), dev(topk_w)
+    c_ref, o_ref, perm_ref, inv_ref, _ = oracle.dispatch(ids, None, w.expert_lo, w.e_hi, want_xs=False)
+    n = int(o_ref[-1])
+    rng = np.random.default_rng(w.seed + 7)
+    # expert outputs of all local assignments (any values do: the FFN has its own tests)
+    ys_all32 = rng.standard_normal((max(n, 1), H)).astype(np.float32)
+    ys_all = ys_all32 if w.act_dtype == "f32" else bf16_bits(ys_all32)
+    ys_all_val = oracle.decode(ys_all).astype(np.float64)
+    per = El // n_nodes
+    for r in ranks:
+        xs_shard = torch.full((A, Hs), 7, dtype=adt, device="cuda")
+        moe.moe_dispatch_shard(cfg, T, x, ids_d, r, m, counts, offsets, perm, inv, xs_shard, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(counts), c_ref)
+        assert np.array_equal(host(offsets), o_ref)
+        assert np.array_equal(host(perm)[:n], perm_ref)
+        assert np.array_equal(host(inv), inv_ref)
+        got = host(xs_shard)[:n]
+        want = x_np[perm_ref // k][:, r * Hs:(r + 1) * Hs]
+        assert np.array_equal(got, want), "rank %d: shard rows differ" % r
+        # staged combine on this rank's column block
+        out_block = torch.full((T, Hs), float("nan"), dtype=torch.float32, device="cuda")
+        ref = None
+        for i in range(n_nodes):
+            lo, hi = w.expert_lo + i * per, w.expert_lo + (i + 1) * per if i < n_nodes - 1 else w.e_hi
+            ci, oi, pi, inv_i, _ = oracle.dispatch(ids, None, lo, hi, want_xs=False)
+            rows = inv_ref[pi]                       # rows of this node's experts, in order
+            blk = np.ascontiguousarray(ys_all[rows][:, r * Hs:(r + 1) * Hs]) if rows.size else \
+                np.zeros((1, Hs), ys_all.dtype)
+            moe.moe_combine_stage(cfg, T, dev(blk), dev(inv_i), w_d, m, int(i > 0), out_block)
+            ref = oracle.combine_stage(ys_all_val[rows][:, r * Hs:(r + 1) * Hs], inv_i, topk_w, ref)
+        torch.cuda.synchronize()
+        got = host(out_block)
+        scale = np.abs(ref).max() + 1e-30
+        if sample_rows is not None:
+            got, ref = got[sample_rows], ref[sample_rows]
+        assert np.isfinite(got).all()
+        err = np.abs(got.astype(np.float64) - ref).max() / scale
+        assert err <= 1e-5, "rank %d: block sum error %.3g" % (r, err)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_shard_and_stage_small(name):
+    w, m, n_nodes = CASES[name]
+    d = inputs(w)
+    ids, tw, _ = oracle_route(w, d["x"], d["gate"])
+    run_case(w, m, n_nodes, ids, tw, range(m))
+
+
+def test_one_rank_equals_plain_entry_points():
+    w, m, n_nodes = CASES["one_rank"]
+    cfg = config_from_workload(w)
+    d = inputs(w)
+    ids, tw, _ = oracle_route(w, d["x"], d["gate"])
+    x = dev(d["x"])
+    T, k, H, A, El = w.T, w.k, w.H, w.T * w.k, w.e_hi - w.expert_lo
+    i32 = dict(dtype=torch.int32, device="cuda")
+    mk = lambda: (torch.empty(El, **i32), torch.empty(El + 1, **i32), torch.empty(A, **i32),
+                  torch.empty(A, **i32), torch.zeros((A, H), dtype=torch.bfloat16, device="cuda"))
+    ws = torch.empty(max(moe.moe_workspace_bytes(cfg, T), 256), dtype=torch.uint8, device="cuda")
+    a, b = mk(), mk()
+    moe.moe_dispatch(cfg, T, x, dev(ids), *a, ws)
+    moe.moe_dispatch_shard(cfg, T, x, dev(ids), 0, 1, *b, ws)
+    torch.cuda.synchronize()
+    n = int(a[1][-1])
+    for u, v in zip(a[:2], b[:2]):
+        assert torch.equal(u, v)
+    assert torch.equal(a[2][:n], b[2][:n]) and torch.equal(a[3], b[3])
+    assert torch.equal(a[4][:n].view(torch.int16), b[4][:n].view(torch.int16))
+    ys = torch.randn((A, H), device="cuda").to(torch.bfloat16)
+    o1 = torch.empty((T, H), dtype=torch.float32, device="cuda")
+    o2 = torch.full((T, H), float("nan"), dtype=torch.float32, device="cuda")
+    moe.moe_combine(cfg, T, ys, a[3], dev(tw), None, o1)
+    moe.moe_combine_stage(cfg, T, ys, a[3], dev(tw), 1, 0, o2)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+
+
+@pytest.mark.parametrize("name,m,n_nodes", [("c4", 2, 4), ("c2p", 8, 8)])
+def test_shard_and_stage_full_size(name, m, n_nodes):
+    """At the benchmark's sizes: routing from the HIP path (its ids are checked
+    against the oracle elsewhere), every integer output bit-exact, the shard
+    rows bit-exact, block sums on sampled tokens."""
+    w = gen.CONFIGS[name]
+    d = inputs(w)
+    from helpers import make_layer
+    L = make_layer(w, d)
+    L.route(dev(d["x"]))
+    torch.cuda.synchronize()
+    ids, tw = host(L.topk_ids), host(L.topk_w)
+    del L
+    torch.cuda.empty_cache()
+    rows = np.unique(np.concatenate([np.arange(64), np.arange(w.T - 64, w.T),
+                                     np.random.default_rng(2).integers(0, w.T, 256)]))
+    run_case(w, m, n_nodes, ids, tw, [0, m - 1], sample_rows=rows)
