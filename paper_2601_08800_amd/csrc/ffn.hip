@@ -10,12 +10,16 @@
 // row); the GEMM grid is sized for the worst case and workgroups past the
 // table's length exit at once, so there is no host round trip.
 //
-// bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation, LDS double buffer,
-// K step 64; LDS tiles are [row][8 pieces of 16 B], piece index XOR (row&7).
-// GEMM-1 loads a gate tile and the matching up tile so that one lane holds g
-// and u of the same element and the SwiGLU is applied in registers.
-// fp8 weights: e4m3 codes are widened to bf16 (exact) on the way into LDS; the
-// 128x128 block scale multiplies the fp32 partial sum of each 128-deep K block.
+// bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation, K step 64.  GEMM-1
+// loads a gate tile and the matching up tile so that one lane holds g and u of
+// the same element and the SwiGLU is applied in registers.  Three kernels, by
+// rows per expert: ffn_gemm8w_kernel (prefill: up to 256 rows x 256 weight rows
+// per workgroup, operands global -> LDS directly, LDS rings), ffn_skinny_kernel
+// (decode and fp8 weights: weight streaming, K split across wavefronts, no LDS
+// staging) and the register-staged ffn_gemm_kernel for the shapes in between.
+// fp8 weights: e4m3 codes are widened to bf16 (exact) in registers or on the
+// way into LDS; the 128x128 block scale multiplies the fp32 partial sum of each
+// 128-deep K block.
 #include <type_traits>
 
 #include "moe_internal.h"
@@ -322,23 +326,22 @@ __device__ __forceinline__ void wait_vmcnt() {
 // 16-byte columns).  Operand fragments are read one K sub-step ahead of the
 // MFMAs that consume them.  Workgroup ids are remapped so that each XCD (own L2)
 // walks a contiguous run of tiles, M tiles of one expert first: neighbours
-// share the expert's weight panel and, one run later, the activation panel.
-// Wavefronts w and w+4 share a SIMD, so every SIMD carries the same amount of
-// MFMA work for any tile height, and while one of them waits (LDS latency,
-// loads, barrier) the other keeps the matrix unit busy.  K step 64 (128-byte
-// rows: whole cache lines per row and load instruction), two LDS stages.
+// share the expert's weight panel and the activation panel.  Wavefronts w and
+// w+4 share a SIMD: while one of them waits (LDS latency, a load instruction
+// being accepted, the barrier) the other keeps the matrix unit busy.  K step 64
+// (128-byte rows: whole cache lines per row and load instruction); weights and
+// activations have LDS rings of their own (see Ring).
 // NBW = valid 32-row blocks of this wavefront's 128 rows (0..4).
-__device__ __forceinline__ int swz2(int row, int piece) {
-  return row * 8 + (piece ^ ((row >> 1) & 7));
-}
-
 // NB = valid 32-row blocks of the tile (1..8), WM = which half of the rows this
-// wavefront computes; both compile-time so the K loop has no branches.  A stage
-// holds NB*32 activation rows and 256 weight rows of 128 B; as many stages as fit
-// in 160 KB of LDS are used as a ring: short tiles (ragged tails, and the
-// 128..160-row tiles chosen for weight-bound shapes) get three or four stages,
-// i.e. two or three K steps of loads in flight, which is what hides HBM latency
-// when the weights are streamed once.
+// wavefront computes; both compile-time so the K loop has no branches.  A weight
+// stage holds 256 rows of 128 B, an activation stage NB*32 rows.  As many whole
+// (activation + weight) stages as fit in the CU's 160 KB of LDS, at most four,
+// give the depth of the weight ring; what is left takes up to two further
+// activation stages (256-row tile: 2 weight + 3 activation stages = 160 KB;
+// 160-row tile: 3 + 3; short tiles up to 4 + 6).  With the rotated K loop below
+// the loads of a step must land three quarters of a step after the previous
+// step's barrier, and the extra activation stage is worth 9 % on the 256-row
+// tile.
 // K step per stage: 64, i.e. 128-byte LDS rows, so that every load instruction
 // moves whole cache lines.  (A K step of 32 would allow four stages for the tall
 // tiles too, but its 64-byte row pieces halve the efficiency of the load path:

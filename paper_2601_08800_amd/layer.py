@@ -55,9 +55,18 @@ class MoELayerShare:
         self.out = e(T, H, dt=torch.float32)
         self.ws = e(max(B.moe_workspace_bytes(cfg, T), 256), dt=torch.uint8)
         self.shared_ys = None
+        # The shared expert depends on x only, not on the routing: by default it is
+        # enqueued on a second stream (default priority) with a workspace of its own,
+        # so its GEMMs fill the CUs that the routing kernels and the tail of the
+        # routed GEMMs leave idle; combine waits for both streams.
+        self.overlap_shared = False
         if self.shared is not None:
             self.shared_ys = e(T, H, dt=adt)
             self.shared_offsets = torch.tensor([0, T], dtype=torch.int32, device=device)
+            if torch.cuda.is_available():
+                self.overlap_shared = True
+                self.ws_shared = e(self.ws.numel(), dt=torch.uint8)
+                self.side_stream = torch.cuda.Stream(device=device)
 
     def route(self, x, logits_in=None, stream=None):
         g = self.gate
@@ -74,11 +83,11 @@ class MoELayerShare:
                          w["w_gate"], w["w_up"], w["w_down"], w.get("s_gate"), w.get("s_up"),
                          w.get("s_down"), self.ys, self.ws, stream)
 
-    def shared_ffn(self, x, stream=None):
+    def shared_ffn(self, x, stream=None, ws=None):
         w = self.shared
         B.moe_expert_ffn(self.cfg, 1, x, self.shared_offsets, self.T, w["w_gate"], w["w_up"],
                          w["w_down"], w.get("s_gate"), w.get("s_up"), w.get("s_down"),
-                         self.shared_ys, self.ws, stream)
+                         self.shared_ys, self.ws if ws is None else ws, stream)
 
     def combine(self, stream=None, ys=None):
         B.moe_combine(self.cfg, self.T, self.ys if ys is None else ys, self.inv, self.topk_w,
@@ -87,13 +96,20 @@ class MoELayerShare:
     def forward(self, x, forced=None, stream=None):
         """One pass of the whole path.  `forced` = (ids, w) device tensors to
         bypass the gate (forced-routing stress case)."""
+        concurrent = self.shared is not None and self.overlap_shared
+        if concurrent:
+            main = torch.cuda.current_stream() if stream is None else stream
+            self.side_stream.wait_stream(main)       # x ready; the previous combine has read shared_ys
+            self.shared_ffn(x, self.side_stream, ws=self.ws_shared)
         if forced is None:
             self.route(x, stream=stream)
         else:
             self.topk_ids, self.topk_w = forced
         self.dispatch(x, stream)
         self.expert_ffn(stream)
-        if self.shared is not None:
+        if concurrent:
+            main.wait_stream(self.side_stream)
+        elif self.shared is not None:
             self.shared_ffn(x, stream)
         self.combine(stream)
         return self.out
