@@ -200,6 +200,22 @@ def main():
         "stages": stages,
     }
 
+    # the same step replayed from a HIP graph (launch overhead off the critical path)
+    try:
+        graph = L.capture(x, forced)
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+        out["hip_graph_replay"] = {"ms_per_step": round(g_ms, 4), "tokens_per_s": round(w.T / (g_ms * 1e-3), 1)}
+        del graph
+    except Exception as exc:            # reported, never fatal for the benchmark line
+        out["hip_graph_replay"] = {"error": str(exc)[:200]}
+
     out["next_rows"] = next_rows(moe, L, w, x, a_loc, tokens_local, max(args.steps, 5))
 
     if not args.no_cpu_baseline:

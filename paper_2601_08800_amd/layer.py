@@ -93,6 +93,24 @@ class MoELayerShare:
         B.moe_combine(self.cfg, self.T, self.ys if ys is None else ys, self.inv, self.topk_w,
                       self.shared_ys, self.out, stream)
 
+    def capture(self, x, forced=None, warmup=2):
+        """Record one pass over `x` (and this object's buffers) into a HIP graph and
+        return it; `graph.replay()` re-runs the pass, e.g. after new data has been
+        copied into `x`.  The library clears its counters with kernels, not memset
+        nodes, and opts into large LDS on a kernel's first launch, which the
+        warm-up passes get out of the way before the capture starts."""
+        side = torch.cuda.Stream(device=self.dev)
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(warmup):
+                self.forward(x, forced)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.forward(x, forced)
+        return graph
+
     def forward(self, x, forced=None, stream=None):
         """One pass of the whole path.  `forced` = (ids, w) device tensors to
         bypass the gate (forced-routing stress case)."""
