@@ -66,9 +66,15 @@ constexpr int kTileRec = 5;
 __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restrict__ offsets,
                                                        int n_experts, int bm, int rows_capacity,
                                                        int32_t* __restrict__ tiles, int max_tiles,
-                                                       int balance) {
+                                                       int balance, int bm_second,
+                                                       int32_t* __restrict__ tiles_second) {
   __shared__ int32_t start[513];
   __shared__ int32_t off[513];
+  // a second workgroup, when launched, builds a second table with its own tile height
+  if (blockIdx.x == 1) {
+    bm = bm_second;
+    tiles = tiles_second;
+  }
   for (int e = threadIdx.x; e <= n_experts; e += blockDim.x) {
     int o = offsets[e];
     o = o < 0 ? 0 : o;
@@ -894,7 +900,8 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
   const int H = c.hidden, I = c.inter_local;
   const int max_mt = rows_capacity / BM + n_experts;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
-                     rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0);
+                     rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0, 0,
+             (int32_t*)nullptr);
   const int nt1 = (I + BN1 - 1) / BN1, nt2 = (H + BN2 - 1) / BN2;
   auto k1 = ffn_gemm_kernel<BM, BN1, WM, WN1, true, FP8>;
   auto k2 = ffn_gemm_kernel<BM, BN2, WM, WN2, false, FP8>;
@@ -923,7 +930,8 @@ void launch_skinny(const moe_config& c, int n_experts, const void* xs, const int
   const int H = c.hidden, I = c.inter_local;
   const int max_mt = rows_capacity / 32 + n_experts;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, 32,
-             rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0);
+             rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0, 0,
+             (int32_t*)nullptr);
   const int nt1 = (I + 31) / 32, nt2 = (H + 63) / 64;
   MOE_LAUNCH(MOE_K_FFN_GEMM1, (ffn_skinny_kernel<true, FP8>), dim3(size_t(max_mt) * nt1), dim3(256),
              0, s, static_cast<const uint16_t*>(xs), w_gate, w_up, s_gate, s_up,
@@ -939,13 +947,20 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   const int H = c.hidden, I = c.inter_local;
   // Few rows per expert means the weights are streamed about once: cap the tile
   // height at 160 rows there, which leaves room for a three-stage ring.
+  // GEMM-2 (K = I_loc is short, N = H wide) is best with 256-row tiles throughout
+  // (measured); when the two heights differ a second workgroup of the table
+  // kernel builds GEMM-2's table.
   const int bm = rows_capacity / n_experts <= 320 ? 160 : 256;
+  const int bm2 = 256;
   const int max_mt = rows_capacity / bm + n_experts;
-  MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, bm,
-             rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 1);
+  const int max_mt2 = rows_capacity / bm2 + n_experts;
+  const int cap = max_mt < ws.max_tiles ? max_mt : ws.max_tiles;
+  int32_t* const tiles2 = bm2 == bm ? ws.tiles : ws.tiles2;
+  MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(bm2 == bm ? 1 : 2), dim3(256), 0, s, offsets,
+             n_experts, bm, rows_capacity, ws.tiles, cap, 1, bm2, tiles2);
   const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
   constexpr int lds = 160 * 1024;         // all of a CU's LDS: the rings of the tallest tile fill it
-  const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt * nt2 + 7) / 8 * 8;
+  const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt2 * nt2 + 7) / 8 * 8;
   auto k1 = ffn_gemm8w_kernel<true>;
   auto k2 = ffn_gemm8w_kernel<false>;
   static bool configured = false;     // LDS above 64 KB must be opted into, once per kernel
@@ -961,7 +976,7 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
              static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
   MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(g2), dim3(512), lds, s,
              static_cast<const uint16_t*>(ws.hmid), static_cast<const uint16_t*>(w_down),
-             (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles, 1);
+             (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, tiles2, 1);
 }
 
 }  // namespace
@@ -976,7 +991,8 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
     const int BM = 64;
     const int max_mt = rows_capacity / BM + n_experts;
     MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
-                       rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0);
+                       rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0, 0,
+             (int32_t*)nullptr);
     MOE_LAUNCH(MOE_K_FFN_GEMM1, ffn_f32_kernel<true>, dim3(size_t(max_mt) * ((I + 63) / 64)), dim3(256), 0,
                        s, static_cast<const float*>(xs), static_cast<const float*>(w_gate),
                        static_cast<const float*>(w_up), static_cast<float*>(ws.hmid), I, H,

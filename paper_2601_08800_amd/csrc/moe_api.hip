@@ -67,6 +67,7 @@ FfnWs carve_ffn(void* ws, int rows_capacity, int n_experts, int I_loc, int abyte
   f.max_tiles = rows_capacity / kMaxTileRows + n_experts + 1;
   size_t off = 0;
   f.tiles = reinterpret_cast<int32_t*>(p + off); off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
+  f.tiles2 = reinterpret_cast<int32_t*>(p + off); off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
   f.hmid = p + off;                              off += align_up(size_t(rows_capacity) * I_loc * abytes);
   f.bytes = off;
   return f;

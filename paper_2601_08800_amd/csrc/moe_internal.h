@@ -44,7 +44,8 @@ DispatchWs carve_dispatch(void* ws, int T, int k, int E_loc);
 // expert FFN
 constexpr int kMaxTileRows = 32;              // smallest M tile any FFN kernel uses
 struct FfnWs {
-  int32_t* tiles;      // [0]=number of M tiles, then (expert,row0,row1) triples
+  int32_t* tiles;      // [0]=number of M tiles, then 5-int tile records
+  int32_t* tiles2;     // a second table of the same capacity (GEMM-2 with another tile height)
   void* hmid;          // [rows_capacity, I_loc] act dtype
   int max_tiles;
   size_t bytes;
