@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--workload", default="c2p", choices=list(DESCR))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the HIP-graph replay and the next_rows measurements (profiling runs)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -199,6 +201,13 @@ def main():
         "roofline": roof,
         "stages": stages,
     }
+
+    if args.no_extras:
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline(w, x_np, gate, experts, shared, forced_np,
+                                               args.cpu_seconds)
+        print(json.dumps(out), flush=True)
+        return 0
 
     # the same step replayed from a HIP graph (launch overhead off the critical path)
     try:
