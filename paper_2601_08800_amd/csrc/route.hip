@@ -196,6 +196,8 @@ __global__ __launch_bounds__(256) void gate_f64_kernel(const void* __restrict__ 
 // each 32 x 64 = two 32x32 MFMA tiles.  LDS tiles are [row][8 pieces of 16 B]
 // with the piece index XOR-ed by (row/2)&7 so that the 16 lanes the LDS serves
 // per cycle fall on 16 different 16-byte columns.
+// K of the gate GEMM is split until about this many workgroups run (2 per CU)
+constexpr int kGateWgTarget = 512;
 constexpr int GBM = 64, GBN = 128, GBK = 64;
 
 __device__ __forceinline__ int swz(int row, int piece) {
@@ -804,12 +806,13 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
     // microseconds up to about 2^28 of them, and needs (almost) no re-scoring
     const bool small = size_t(T) * E * H <= (size_t(1) << 28);
     if (bf16 && !small) {
-      // fewer tiles than CUs: split K so that about one workgroup per CU runs; each
-      // split keeps at least 8 K steps
+      // few tiles: split K so that about two workgroups per CU run (one workgroup is
+      // one wavefront per SIMD, which hides no latency); each split keeps at least 8
+      // K steps
       const int blocks = ((T + GBM - 1) / GBM) * ((E + GBN - 1) / GBN);
       const int ksteps = (H + GBK - 1) / GBK;
       int nsplit = 1;
-      while (nsplit < kGateMaxSplit && blocks * nsplit * 2 <= 256 && ksteps / (nsplit * 2) >= 8) nsplit *= 2;
+      while (nsplit < kGateMaxSplit && blocks * nsplit * 2 <= kGateWgTarget && ksteps / (nsplit * 2) >= 8) nsplit *= 2;
       const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN, nsplit);
       MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(256), 0, s,
                  static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
