@@ -630,7 +630,7 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
   // token row once per batch of CB experts, lane-strided 16-byte pieces, four
   // pieces per lane and expert in flight; the lane sums are combined by a fixed
   // butterfly.
-  constexpr int CB = 4;
+  constexpr int CB = 4;   // 6 and 8 measured slower (register pressure)
   auto exact_logits = [&](int t, int n) {
     if (logits_in) {
       for (int q = lane; q < n; q += 64) {
