@@ -192,10 +192,14 @@ __global__ __launch_bounds__(256) void gate_f64_kernel(const void* __restrict__ 
 }
 
 // ------------------------------------------ stage 1 (bf16): MFMA gate GEMM
-// Block tile 64 tokens x 128 experts, K step 64, 4 wavefronts as 2 (M) x 2 (N),
-// each 32 x 64 = two 32x32 MFMA tiles.  LDS tiles are [row][8 pieces of 16 B]
-// with the piece index XOR-ed by (row/2)&7 so that the 16 lanes the LDS serves
-// per cycle fall on 16 different 16-byte columns.
+// Block tile 64 tokens x 128 experts, K step 64, 8 wavefronts as 2 (M) x 4 (N),
+// each one 32x32 MFMA tile (16 fp32 accumulators flushed into 16 fp64 sums every
+// K step): the flush is as much VALU work as the MFMAs are matrix work, so many
+// light wavefronts per SIMD (three workgroups fit a CU) overlap the two and the
+// register-staged loads better than four wavefronts with two tiles each did.
+// LDS tiles are [row][8 pieces of 16 B] with the piece index XOR-ed by (row/2)&7
+// so that the 16 lanes the LDS serves per cycle fall on 16 different 16-byte
+// columns.
 // K of the gate GEMM is split until about this many workgroups run (2 per CU)
 constexpr int kGateWgTarget = 512;
 constexpr int GBM = 64, GBN = 128, GBK = 64;
@@ -205,17 +209,15 @@ __device__ __forceinline__ int swz(int row, int piece) {
 }
 
 template <int CHAIN_STEPS>
-__global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restrict__ x,
-                                                       const uint16_t* __restrict__ gate_w, int T,
-                                                       int H, int E, float* __restrict__ logits,
-                                                       float* __restrict__ xnorm2) {
+__global__ __launch_bounds__(512) void gate_mfma_kernel(const uint16_t* __restrict__ x,
+                                                        const uint16_t* __restrict__ gate_w, int T,
+                                                        int H, int E, float* __restrict__ logits,
+                                                        float* __restrict__ xnorm2) {
   __shared__ uint4 As[2][GBM * 8];
   __shared__ uint4 Bs[2][GBN * 8];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   const int m0 = blockIdx.x * GBM, n0 = blockIdx.y * GBN;
-  // K split: slab z of gridDim.z covers K steps [z*per, (z+1)*per) and writes its own
-  // partial logits and partial row norms
   const int all_steps = (H + GBK - 1) / GBK;
   const int per_split = (all_steps + gridDim.z - 1) / gridDim.z;
   const int ks0 = blockIdx.z * per_split;
@@ -223,48 +225,40 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
   logits += size_t(blockIdx.z) * T * E;
   xnorm2 += size_t(blockIdx.z) * T;
 
-  // global -> register staging: A 2 pieces / thread, B 4 pieces / thread
-  const int lrow = tid >> 3, lpiece = tid & 7;
-  uint4 ra[2], rb[4];
-  float xsq[2] = {0.f, 0.f};
+  // global -> register staging: A 1 piece / thread, B 2 pieces / thread
+  const int lrow = tid >> 3, lpiece = tid & 7;        // lrow 0..63
+  uint4 ra, rb[2];
+  float xsq = 0.f;
   auto gload = [&](int ks) {
     const int kcol = (ks0 + ks) * GBK + lpiece * 8;
     const bool kin = kcol < H;
+    int r = m0 + lrow;
+    r = r < T ? r : T - 1;
+    ra = kin ? *reinterpret_cast<const uint4*>(x + size_t(r) * H + kcol) : make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      int r = m0 + lrow + 32 * i;
-      r = r < T ? r : T - 1;
-      ra[i] = kin ? *reinterpret_cast<const uint4*>(x + size_t(r) * H + kcol) : make_uint4(0, 0, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int r = n0 + lrow + 32 * i;
-      r = r < E ? r : E - 1;
-      rb[i] = kin ? *reinterpret_cast<const uint4*>(gate_w + size_t(r) * H + kcol) : make_uint4(0, 0, 0, 0);
+      int n = n0 + lrow + 64 * i;
+      n = n < E ? n : E - 1;
+      rb[i] = kin ? *reinterpret_cast<const uint4*>(gate_w + size_t(n) * H + kcol) : make_uint4(0, 0, 0, 0);
     }
   };
   auto lstore = [&](int buf) {
+    As[buf][swz(lrow, lpiece)] = ra;
+    const uint32_t v[4] = {ra.x, ra.y, ra.z, ra.w};
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      As[buf][swz(lrow + 32 * i, lpiece)] = ra[i];
-      const uint32_t v[4] = {ra[i].x, ra[i].y, ra[i].z, ra[i].w};
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float lo = bf16_bits_to_f32(v[q] & 0xffffu), hi = bf16_bits_to_f32(v[q] >> 16);
-        xsq[i] = fmaf(lo, lo, xsq[i]);
-        xsq[i] = fmaf(hi, hi, xsq[i]);
-      }
+    for (int q = 0; q < 4; ++q) {
+      const float lo = bf16_bits_to_f32(v[q] & 0xffffu), hi = bf16_bits_to_f32(v[q] >> 16);
+      xsq = fmaf(lo, lo, xsq);
+      xsq = fmaf(hi, hi, xsq);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) Bs[buf][swz(lrow + 32 * i, lpiece)] = rb[i];
+    for (int i = 0; i < 2; ++i) Bs[buf][swz(lrow + 64 * i, lpiece)] = rb[i];
   };
 
-  f32x16 acc[2];
-  double dsum[2][16];
+  f32x16 acc;
+  double dsum[16];
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) { acc[j][i] = 0.f; dsum[j][i] = 0.0; }
+  for (int i = 0; i < 16; ++i) { acc[i] = 0.f; dsum[i] = 0.0; }
 
   gload(0);
   lstore(0);
@@ -276,44 +270,33 @@ __global__ __launch_bounds__(256) void gate_mfma_kernel(const uint16_t* __restri
     for (int kk = 0; kk < 4; ++kk) {
       const int piece = kk * 2 + (lane >> 5);
       const uint4 av = As[buf][swz(wm * 32 + (lane & 31), piece)];
-      const bf16x8 a = __builtin_bit_cast(bf16x8, av);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const uint4 bv = Bs[buf][swz(wn * 64 + j * 32 + (lane & 31), piece)];
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[j], 0, 0, 0);
-      }
+      const uint4 bv = Bs[buf][swz(wn * 32 + (lane & 31), piece)];
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av),
+                                                    __builtin_bit_cast(bf16x8, bv), acc, 0, 0, 0);
     }
     if ((ks + 1) % CHAIN_STEPS == 0 || ks + 1 == ksteps) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { dsum[j][i] += (double)acc[j][i]; acc[j][i] = 0.f; }
+      for (int i = 0; i < 16; ++i) { dsum[i] += (double)acc[i]; acc[i] = 0.f; }
     }
     if (ks + 1 < ksteps) lstore(buf ^ 1);
     __syncthreads();
   }
 
   // D layout of the 32x32 MFMA: lane l, register i -> row (i/4)*8 + (l/32)*4 + i%4, col l%32
+  const int col = n0 + wn * 32 + (lane & 31);
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = m0 + wm * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
-      if (row < T && col < E) logits[size_t(row) * E + col] = (float)dsum[j][i];
-    }
+  for (int i = 0; i < 16; ++i) {
+    const int row = m0 + wm * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+    if (row < T && col < E) logits[size_t(row) * E + col] = (float)dsum[i];
   }
   // squared row norms: the 8 threads with equal lrow hold one row's pieces
   if (blockIdx.y == 0) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      float s = xsq[i];
-      s += __shfl_xor(s, 1);
-      s += __shfl_xor(s, 2);
-      s += __shfl_xor(s, 4);
-      const int r = m0 + lrow + 32 * i;
-      if (lpiece == 0 && r < T) xnorm2[r] = s * 1.001f;
-    }
+    float s = xsq;
+    s += __shfl_xor(s, 1);
+    s += __shfl_xor(s, 2);
+    s += __shfl_xor(s, 4);
+    const int r = m0 + lrow;
+    if (lpiece == 0 && r < T) xnorm2[r] = s * 1.001f;
   }
 }
 
@@ -814,7 +797,7 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
       int nsplit = 1;
       while (nsplit < kGateMaxSplit && blocks * nsplit * 2 <= kGateWgTarget && ksteps / (nsplit * 2) >= 8) nsplit *= 2;
       const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN, nsplit);
-      MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(256), 0, s,
+      MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(512), 0, s,
                  static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
                  ws.logits, ws.xnorm2);
       sc.nsplit = nsplit;
