@@ -758,10 +758,12 @@ __global__ __launch_bounds__(256) void ffn_skinny_kernel(
           const uint32_t c0 = (kk & 1) ? v.z : v.x, c1 = (kk & 1) ? v.w : v.y;
           const f32x2 p0 = __builtin_amdgcn_cvt_pk_f32_fp8(c0, false), p1 = __builtin_amdgcn_cvt_pk_f32_fp8(c0, true);
           const f32x2 p2 = __builtin_amdgcn_cvt_pk_f32_fp8(c1, false), p3 = __builtin_amdgcn_cvt_pk_f32_fp8(c1, true);
-          const uint4 w8 = make_uint4((__float_as_uint(p0[0]) >> 16) | (__float_as_uint(p0[1]) & 0xffff0000u),
-                                      (__float_as_uint(p1[0]) >> 16) | (__float_as_uint(p1[1]) & 0xffff0000u),
-                                      (__float_as_uint(p2[0]) >> 16) | (__float_as_uint(p2[1]) & 0xffff0000u),
-                                      (__float_as_uint(p3[0]) >> 16) | (__float_as_uint(p3[1]) & 0xffff0000u));
+          // upper halves of the two floats side by side (the lower halves are zero:
+          // an e4m3 value has three mantissa bits), one byte permute per pair
+          auto pack = [](f32x2 p) {
+            return __builtin_amdgcn_perm(__float_as_uint(p[1]), __float_as_uint(p[0]), 0x07060302u);
+          };
+          const uint4 w8 = make_uint4(pack(p0), pack(p1), pack(p2), pack(p3));
           part[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, r.a[kk]),
                                                             __builtin_bit_cast(bf16x8, w8), part[j], 0, 0, 0);
         }
