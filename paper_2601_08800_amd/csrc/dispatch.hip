@@ -176,6 +176,134 @@ __global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4* __res
   }
 }
 
+// Few assignments (A <= kSmallA): the whole dispatch in one launch.  Every
+// workgroup rebuilds the same index in its own LDS (count per sub-chunk, scan
+// per expert, scan over experts, place: the steps and the order of the kernels
+// above, so the permutation is the same), workgroup 0 stores it, and each
+// workgroup then copies the rows of its four tokens.  The redundant index work
+// is a few microseconds on otherwise idle CUs and replaces three launches.
+// LDS: hist[n_sub][E_loc] | slot[n_sub*64] | cnt[E_loc] | offs[E_loc+1].
+constexpr int kSmallA = 4096;
+constexpr size_t kSmallLds = 60 * 1024;
+inline size_t small_lds_bytes(int E_loc, int n_sub) {
+  return (size_t(n_sub) * E_loc + size_t(n_sub) * kSub + 2 * size_t(E_loc) + 1) * sizeof(int32_t);
+}
+
+template <int PIECES>
+__global__ __launch_bounds__(256) void dispatch_small_kernel(
+    const int32_t* __restrict__ ids, int A, int e_lo, int E_loc, int n_sub,
+    int32_t* __restrict__ counts, int32_t* __restrict__ offsets_out, int32_t* __restrict__ perm,
+    int32_t* __restrict__ inv, const uint4* __restrict__ x, uint4* __restrict__ xs, int T, int k,
+    int src16, int col16, int row16) {
+  extern __shared__ int32_t lds[];
+  int32_t* const hist = lds;                         // [n_sub][E_loc]
+  int32_t* const slot = hist + n_sub * E_loc;        // [n_sub*64]: (e << 6 | rank), then position
+  int32_t* const cnt = slot + n_sub * kSub;          // [E_loc]
+  int32_t* const offs = cnt + E_loc;                 // [E_loc + 1]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const bool first = blockIdx.x == 0;
+  for (int i = tid; i < n_sub * E_loc; i += 256) hist[i] = 0;
+  __syncthreads();
+  // 1. count: ballots find the lanes of a sub-chunk that share an expert
+  for (int sub = wave; sub < n_sub; sub += 4) {
+    const int a = sub * kSub + lane;
+    int e = -1;
+    if (a < A) {
+      e = ids[a] - e_lo;
+      if (e < 0 || e >= E_loc) e = -1;
+    }
+    int rank = 0;
+    uint64_t todo = __ballot(e >= 0);
+    while (todo) {
+      const int leader = __ffsll((unsigned long long)todo) - 1;
+      const int e0 = __shfl(e, leader);
+      const uint64_t m = __ballot(e == e0);
+      if (e == e0) rank = __popcll(m & lanemask_lt());
+      if (lane == leader) hist[sub * E_loc + e0] = __popcll(m);
+      todo &= ~m;
+    }
+    slot[a] = e >= 0 ? (e << 6 | rank) : -1;
+  }
+  __syncthreads();
+  // 2. scan over the sub-chunks, one thread per expert
+  for (int e = tid; e < E_loc; e += 256) {
+    int run = 0;
+    for (int sb = 0; sb < n_sub; ++sb) {
+      const int c = hist[sb * E_loc + e];
+      hist[sb * E_loc + e] = run;
+      run += c;
+    }
+    cnt[e] = run;
+    if (first) counts[e] = run;
+  }
+  __syncthreads();
+  // 3. offsets = exclusive scan of the counts (one wavefront)
+  if (wave == 0) {
+    const int per = (E_loc + 63) / 64;
+    const int x0 = lane * per, x1 = (x0 + per < E_loc) ? x0 + per : E_loc;
+    int sum = 0;
+    for (int i = x0; i < x1; ++i) sum += cnt[i];
+    int incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
+    }
+    int run = incl - sum;
+    for (int i = x0; i < x1; ++i) {
+      offs[i] = run;
+      if (first) offsets_out[i] = run;
+      run += cnt[i];
+    }
+    if (lane == 63) {
+      offs[E_loc] = incl;
+      if (first) offsets_out[E_loc] = incl;
+    }
+  }
+  __syncthreads();
+  // 4. place
+  for (int a = tid; a < A; a += 256) {
+    const int sl = slot[a];
+    int pos = -1;
+    if (sl >= 0) {
+      const int e = sl >> 6;
+      pos = offs[e] + hist[(a / kSub) * E_loc + e] + (sl & 63);
+      if (first) perm[pos] = a;
+    }
+    slot[a] = pos;
+    if (first) inv[a] = pos;
+  }
+  __syncthreads();
+  // 5. copy the rows of this workgroup's tokens (one wavefront per token)
+  const int t = blockIdx.x * 4 + wave;
+  if (t >= T) return;
+  int pos = -1;
+  if (lane < k) pos = slot[t * k + lane];
+  const uint64_t have = __ballot(pos >= 0);
+  if (!have) return;
+  const uint4* src = x + size_t(t) * src16 + col16;
+  for (int c0 = 0; c0 < row16; c0 += 64 * PIECES) {
+    uint4 v[PIECES];
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+      const int c = c0 + i * 64 + lane;
+      if (c < row16) v[i] = nt_load16(src + c);
+    }
+    uint64_t m = have;
+    while (m) {
+      const int j = __ffsll((unsigned long long)m) - 1;
+      m &= m - 1;
+      const int p = __shfl(pos, j);
+      uint4* dst = xs + size_t(p) * row16;
+#pragma unroll
+      for (int i = 0; i < PIECES; ++i) {
+        const int c = c0 + i * 64 + lane;
+        if (c < row16) nt_store16(dst + c, v[i]);
+      }
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int32_t* ids,
@@ -186,6 +314,16 @@ hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int3
   const int A = T * k;
   const int E_loc = c.expert_hi - c.expert_lo;
   const int n_sub = (A + kSub - 1) / kSub;
+  // column window of TP rank tp_rank of tp_size (the whole row for 0 of 1)
+  const int src16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
+  const int row16 = src16 / tp_size;
+  if (A <= kSmallA && small_lds_bytes(E_loc, n_sub) <= kSmallLds) {
+    MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_small_kernel<8>, dim3((T + 3) / 4), dim3(256),
+               small_lds_bytes(E_loc, n_sub), s, ids, A, c.expert_lo, E_loc, n_sub, counts, offsets,
+               perm, inv, static_cast<const uint4*>(x), static_cast<uint4*>(xs), T, k, src16,
+               tp_rank * row16, row16);
+    return hipGetLastError();
+  }
   const dim3 grid_idx((n_sub + 3) / 4), block_idx(256);
   MOE_LAUNCH(MOE_K_DISPATCH_HIST, dispatch_count_kernel, grid_idx, block_idx, 0, s, ids, A,
              c.expert_lo, E_loc, n_sub, ws.block_hist, inv);
@@ -193,9 +331,6 @@ hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int3
              n_sub, counts);
   MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_place_kernel, dim3((A + 255) / 256), block_idx, 0, s,
              ids, A, c.expert_lo, E_loc, n_sub, ws.block_hist, counts, offsets, perm, inv);
-  // column window of TP rank tp_rank of tp_size (the whole row for 0 of 1)
-  const int src16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
-  const int row16 = src16 / tp_size;
   MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_gather_kernel<8>, dim3((T + 3) / 4), dim3(256), 0, s,
              static_cast<const uint4*>(x), inv, static_cast<uint4*>(xs), T, k, src16,
              tp_rank * row16, row16);

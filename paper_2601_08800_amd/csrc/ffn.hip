@@ -102,24 +102,32 @@ __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restric
       start[e] = run;
       run += m > 0 ? (m + bm - 1) / bm : 0;
     }
-    if (lane == 63) tiles[0] = incl < max_tiles ? incl : max_tiles;
+    if (lane == 63) {
+      start[n_experts] = incl;
+      tiles[0] = incl < max_tiles ? incl : max_tiles;
+    }
   }
   __syncthreads();
-  for (int e = threadIdx.x; e < n_experts; e += blockDim.x) {
+  // one thread per tile: its expert is the last one whose first tile is <= t
+  const int n_tiles = start[n_experts] < max_tiles ? start[n_experts] : max_tiles;
+  for (int t = threadIdx.x; t < n_tiles; t += blockDim.x) {
+    int e = 0, e_hi = n_experts;
+    while (e_hi - e > 1) {
+      const int mid = (e + e_hi) >> 1;
+      if (start[mid] <= t) e = mid; else e_hi = mid;
+    }
     const int lo = off[e], hi = off[e + 1];
-    int t = start[e];
     int step = bm;
-    if (balance && hi > lo) {
+    if (balance) {
       const int nt = (hi - lo + bm - 1) / bm;
       step = (((hi - lo + nt - 1) / nt) + 31) / 32 * 32;
     }
-    for (int r = lo; r < hi && t < max_tiles; r += step, ++t) {
-      tiles[1 + kTileRec * t] = e;
-      tiles[2 + kTileRec * t] = r;
-      tiles[3 + kTileRec * t] = (r + step < hi) ? r + step : hi;
-      tiles[4 + kTileRec * t] = start[e];
-      tiles[5 + kTileRec * t] = (hi - lo + step - 1) / step;
-    }
+    const int r = lo + (t - start[e]) * step;
+    tiles[1 + kTileRec * t] = e;
+    tiles[2 + kTileRec * t] = r;
+    tiles[3 + kTileRec * t] = (r + step < hi) ? r + step : hi;
+    tiles[4 + kTileRec * t] = start[e];
+    tiles[5 + kTileRec * t] = (hi - lo + step - 1) / step;
   }
 }
 

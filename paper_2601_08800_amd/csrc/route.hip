@@ -13,6 +13,8 @@
 //   3. re-score    one workgroup per listed token: the experts whose key
 //                  interval reaches the selection get an fp64 dot product and
 //                  the selection is redone in fp64
+// Decode-sized batches (T*E*H up to 2^28) skip all three: one kernel computes
+// every logit in fp64 and selects on fp64 keys.
 // Error model of stage 1 for a chain of n bf16 products (exact in fp32) added
 // in fp32: every addition is off by at most one ulp of the running sum, so
 // |error| <= 2n * 2^-24 * sum|x_h w_h| <= 2n * 2^-24 * |x|_2 |w|_2.
@@ -167,11 +169,9 @@ __global__ __launch_bounds__(256) void gate_wnorm_kernel(const void* __restrict_
   if (lane == 0) wnorm2[e] = (float)(s * (1.0 + 1e-6));
 }
 
-// ----------------------- stage 1 (fp32 inputs, or few tokens): fp64 VALU gate
+// ------------------------ stage 1 (fp32 inputs, many tokens): fp64 VALU gate
 // One workgroup per token; each wavefront takes every 4th expert.  Exact
-// products, fp64 sums: the logits are good to the fp32 store.  Used for fp32
-// activations and for decode-sized batches, where a tiled GEMM would leave the
-// chip idle and the fp64 work is negligible.
+// products, fp64 sums: the logits are good to the fp32 store.
 template <bool BF16>
 __global__ __launch_bounds__(256) void gate_f64_kernel(const void* __restrict__ x,
                                                       const void* __restrict__ gate_w, int T,
@@ -742,6 +742,111 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
   }
 }
 
+// -------------------- few tokens: gate, scores and top-k of a token in one pass
+// One workgroup of sixteen wavefronts per token.  The wavefronts share out the experts and
+// compute every logit exactly (fp64 sums of exact products, CB experts per walk
+// over the token row); the first wavefront then builds fp64 keys for all experts
+// and takes the group limit, the top-k and the weights in fp64.  No fast pass,
+// no error intervals and nothing to re-score: at decode sizes the T*E*H fused
+// multiply-adds cost less than the launches they replace.
+template <int EPL, bool BF16>
+__global__ __launch_bounds__(1024) void route_exact_kernel(
+    SelCfg c, int H, const void* __restrict__ x, const void* __restrict__ gate_w,
+    const float* __restrict__ logit_bias, const float* __restrict__ select_bias,
+    int32_t* __restrict__ ids, float* __restrict__ w, int32_t* __restrict__ counters) {
+  __shared__ double zx[EPL * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.x;
+  if (t == 0 && threadIdx.x < 64) counters[threadIdx.x] = 0;   // nothing is re-scored
+  const size_t eb = BF16 ? 2 : 4;
+  const char* xrow = static_cast<const char*>(x) + size_t(t) * H * eb;
+  const int n16 = int(H * eb / 16);
+  const int per = (c.E + 15) / 16;
+  const int e_begin = min(c.E, wave * per), e_end = min(c.E, e_begin + per);
+  constexpr int CB = 4, U = 2;
+  for (int e0 = e_begin; e0 < e_end; e0 += CB) {
+    double acc[CB];
+    const char* wrow[CB];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+      acc[i] = 0.0;
+      wrow[i] = static_cast<const char*>(gate_w) + size_t(min(e0 + i, e_end - 1)) * H * eb;
+    }
+    for (int p0 = 0; p0 < n16; p0 += 64 * U) {
+      uint4 a[U], b[CB][U];
+      bool in[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        int p = p0 + u * 64 + lane;
+        in[u] = p < n16;
+        p = in[u] ? p : n16 - 1;
+        a[u] = *reinterpret_cast<const uint4*>(xrow + size_t(p) * 16);
+#pragma unroll
+        for (int i = 0; i < CB; ++i) b[i][u] = *reinterpret_cast<const uint4*>(wrow[i] + size_t(p) * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+          const double d = piece_dot64<BF16>(a[u], b[i][u], 0.0);
+          acc[i] += in[u] ? d : 0.0;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+      double z = wave_sum(acc[i]);
+      if (e0 + i < e_end && lane == 0) {
+        if (logit_bias) z += (double)logit_bias[e0 + i];
+        zx[e0 + i] = z;
+      }
+    }
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  Keys<double, EPL> D;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int e = i * 64 + lane;
+    D.key[i] = -INFINITY; D.sc[i] = 0.0; D.eps[i] = 0.0;
+    if (e < c.E) {
+      const double z = zx[e];
+      if (c.score_fn == MOE_SCORE_SOFTMAX) {
+        D.key[i] = z; D.sc[i] = z;
+      } else {
+        const double sg = 1.0 / (1.0 + exp(-z));
+        D.sc[i] = sg;
+        D.key[i] = sg + (select_bias ? (double)select_bias[e] : 0.0);
+      }
+    }
+  }
+  uint64_t kept = 0;
+  if (c.G > 1) {
+    Groups<double> Gd;
+    group_stage<double, EPL>(c, D, lane, Gd);
+    kept = Gd.kept;
+  }
+  const uint32_t elig = eligible_mask<EPL>(c, kept, lane);
+  Picks<double> Q;
+  topk_stage<double, EPL>(c, D, elig, lane, Q);
+  const double wt = pick_weight<double, EPL>(c, D, Q, lane);
+  if (lane < c.k) {
+    ids[size_t(t) * c.k + lane] = Q.id;
+    w[size_t(t) * c.k + lane] = (float)wt;
+  }
+}
+
+template <int EPL>
+void launch_route_exact(const SelCfg& sc, const moe_config& c, int T, const void* x,
+                        const void* gate_w, const float* logit_bias, const float* select_bias,
+                        int32_t* ids, float* w, const RouteWs& ws, hipStream_t s) {
+  if (c.act_dtype == MOE_BF16)
+    MOE_LAUNCH(MOE_K_GATE_GEMM, (route_exact_kernel<EPL, true>), dim3(T), dim3(1024), 0, s, sc,
+               c.hidden, x, gate_w, logit_bias, select_bias, ids, w, ws.counters);
+  else
+    MOE_LAUNCH(MOE_K_GATE_GEMM, (route_exact_kernel<EPL, false>), dim3(T), dim3(1024), 0, s, sc,
+               c.hidden, x, gate_w, logit_bias, select_bias, ids, w, ws.counters);
+}
+
 template <int EPL>
 void launch_select_and_recheck(const SelCfg& sc, const moe_config& c, int T, const void* x,
                                const void* gate_w, const float* logit_bias,
@@ -775,6 +880,17 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   sc.E = E; sc.k = c.top_k; sc.score_fn = c.score_fn; sc.renormalize = c.renormalize;
   sc.G = c.n_groups; sc.Kg = c.topk_groups; sc.gn = c.group_score_n; sc.scale = c.routed_scale;
   sc.chain_err = 0.f; sc.have_norms = 0; sc.nsplit = 1; sc.T = T;
+  const int epl = (E + 63) / 64;
+  // decode-sized batches: the exact gate costs T*E*H fp64 fused multiply-adds, a
+  // few microseconds up to about 2^28 of them: one kernel does the whole stage
+  const bool small = size_t(T) * E * H <= (size_t(1) << 28);
+  if (!logits_in && small) {
+    if (epl <= 1) launch_route_exact<1>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
+    else if (epl <= 2) launch_route_exact<2>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
+    else if (epl <= 4) launch_route_exact<4>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
+    else launch_route_exact<8>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
+    return hipGetLastError();
+  }
   const void* gw_for_norm = logits_in ? nullptr : gate_w;
   if (bf16)
     MOE_LAUNCH(MOE_K_GATE_NORMS, gate_wnorm_kernel<true>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm, E,
@@ -785,10 +901,7 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   if (!logits_in) {
     logits = ws.logits;
     sc.have_norms = 1;
-    // decode-sized batches: the fp64 gate costs T*E*H fused multiply-adds, a few
-    // microseconds up to about 2^28 of them, and needs (almost) no re-scoring
-    const bool small = size_t(T) * E * H <= (size_t(1) << 28);
-    if (bf16 && !small) {
+    if (bf16) {
       // few tiles: split K so that about two workgroups per CU run (one workgroup is
       // one wavefront per SIMD, which hides no latency); each split keeps at least 8
       // K steps
@@ -807,17 +920,12 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
       // product per addition and per slab store
       sc.chain_err = (2.f * kGateChainSteps * GBK + 2.f + 2.f * (nsplit - 1)) * kUlp;
     } else {
-      if (bf16)
-        MOE_LAUNCH(MOE_K_GATE_GEMM, gate_f64_kernel<true>, dim3(T), dim3(256), 0, s, x, gate_w, T,
-                   H, E, ws.logits, ws.xnorm2);
-      else
-        MOE_LAUNCH(MOE_K_GATE_GEMM, gate_f64_kernel<false>, dim3(T), dim3(256), 0, s, x, gate_w, T,
-                   H, E, ws.logits, ws.xnorm2);
+      MOE_LAUNCH(MOE_K_GATE_GEMM, gate_f64_kernel<false>, dim3(T), dim3(256), 0, s, x, gate_w, T,
+                 H, E, ws.logits, ws.xnorm2);
       // fp64 sums: the only error is the fp32 store, covered by the 2 ulp term
       sc.chain_err = 1e-12f;
     }
   }
-  const int epl = (E + 63) / 64;
   if (epl <= 1)
     launch_select_and_recheck<1>(sc, c, T, x, gate_w, logit_bias, select_bias, logits_in, logits, ids, w, ws, s);
   else if (epl <= 2)

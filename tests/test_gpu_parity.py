@@ -92,6 +92,38 @@ def test_route_recheck_counter_and_determinism():
     assert np.array_equal(a[0], host(L.topk_ids)) and np.array_equal(a[1], host(L.topk_w))
 
 
+# Token counts past the decode-size threshold of the router (T*E*H > 2^28), so the
+# tiled bf16 gate GEMM, the interval test and the fp64 re-scoring run, at sizes
+# the oracle still scores in seconds: ragged T / E / H tails, with and without a
+# split K range, soft-max with a logit bias and sigmoid with a group limit.
+TILED_GATE = {
+    "softmax_ragged_splitk": gen.CONFIGS["c2p"].replace(name="softmax_ragged_splitk", T=1237, H=1096,
+                                                        E=200, k=6, I=64),
+    "softmax_bias_one_slab": gen.CONFIGS["c3"].replace(name="softmax_bias_one_slab", T=4500, H=512,
+                                                       E=128, k=8, I=64, expert_lo=0, expert_hi=4),
+    "sigmoid_groups_splitk": gen.CONFIGS["c4"].replace(name="sigmoid_groups_splitk", T=2100, H=1024,
+                                                       E=192, k=6, I=128, n_groups=6, topk_groups=3,
+                                                       expert_lo=0, expert_hi=8),
+}
+
+
+@pytest.mark.parametrize("name", list(TILED_GATE))
+def test_route_tiled_gate_matches_oracle(name):
+    w = TILED_GATE[name]
+    assert w.T * w.E * w.H > 2 ** 28
+    print("case", name, flush=True)
+    d = inputs(w)
+    L = make_layer(w, d)
+    L.route(dev(d["x"]))
+    torch.cuda.synchronize()
+    n_re = int(L.ws[:4].view(torch.int32).item())
+    ids_ref, w_ref, margin = oracle_route(w, d["x"], d["gate"])
+    n_amb = check_routing(host(L.topk_ids), host(L.topk_w), ids_ref, w_ref, margin,
+                          w.routed_scale, name)
+    print("re-scored", n_re, "of", w.T, "; fp64-ambiguous", n_amb, flush=True)
+    assert 0 <= n_re <= w.T
+
+
 @pytest.mark.parametrize("E,k,score,G,Kg,gn", [
     (8, 2, "softmax", 1, 1, 0), (64, 6, "softmax", 1, 1, 0), (100, 8, "softmax", 1, 1, 0),
     (128, 8, "softmax", 1, 1, 0), (256, 8, "sigmoid", 8, 4, 2), (256, 8, "sigmoid", 1, 1, 0),
