@@ -3,7 +3,8 @@
 // A stable counting sort of the local assignments by expert, with no atomics
 // anywhere (so the permutation is unique and repeatable):
 //   1. count   one wavefront per sub-chunk of 64 consecutive assignments counts
-//              them per local expert with ballots (no atomics) and notes every
+//              them per local expert with ballots (one per bit of the expert
+//              index, no atomics) and notes every
 //              assignment's rank among its expert's assignments of the sub-chunk
 //   2. scan    per expert (one wavefront each) an exclusive scan over the
 //              sub-chunks -> counts; offsets = exclusive scan over experts,
@@ -34,9 +35,23 @@ __device__ __forceinline__ uint64_t lanemask_lt() {
   return (uint64_t(1) << (threadIdx.x & 63)) - 1;
 }
 
+// Lanes of the wavefront that hold the same local expert as this lane: one
+// ballot per bit of the expert index (at most 9), each narrowing the set to the
+// lanes that agree with this lane on that bit.  Meaningful where e >= 0.
+__device__ __forceinline__ uint64_t same_expert_lanes(int e, int E_loc) {
+  uint64_t same = __ballot(e >= 0);
+  const int nbits = E_loc > 1 ? 32 - __clz(E_loc - 1) : 0;
+  for (int b = 0; b < nbits; ++b) {
+    const bool bit = (e >> b) & 1;
+    const uint64_t m = __ballot(bit);
+    same &= bit ? m : ~m;
+  }
+  return same;
+}
+
 // One wavefront per sub-chunk of 64 consecutive flat assignments.  The lanes
-// that go to the same local expert find each other with ballots (one round per
-// distinct expert present), which yields, without atomics, the count per expert
+// that go to the same local expert find each other with ballots, which yields,
+// without atomics, the count per expert
 // and the rank of every assignment among its expert's assignments of the
 // sub-chunk.  Counts go to hist[E_loc][n_sub] (built in a wavefront-private LDS
 // row, so absent experts get their zero), ranks are parked in inv[].
@@ -55,15 +70,11 @@ __global__ __launch_bounds__(256) void dispatch_count_kernel(
   }
   int32_t* row = cnt[wave];                    // same-wavefront LDS accesses execute in order
   for (int x = lane; x < E_loc; x += 64) row[x] = 0;
+  const uint64_t same = same_expert_lanes(e, E_loc);
   int rank = -1;
-  uint64_t todo = __ballot(e >= 0);
-  while (todo) {                               // one round per distinct expert
-    const int leader = __ffsll((unsigned long long)todo) - 1;
-    const int e0 = __shfl(e, leader);
-    const uint64_t m = __ballot(e == e0);
-    if (e == e0) rank = __popcll(m & lanemask_lt());
-    if (lane == leader) row[e0] = __popcll(m);
-    todo &= ~m;
+  if (e >= 0) {
+    rank = __popcll(same & lanemask_lt());
+    if (rank == 0) row[e] = __popcll(same);    // the lowest lane of each expert present
   }
   if (a < A) inv[a] = rank;                    // -1: expert not local
   for (int x = lane; x < E_loc; x += 64) hist[size_t(x) * n_sub + sub] = row[x];
@@ -212,15 +223,11 @@ __global__ __launch_bounds__(256) void dispatch_small_kernel(
       e = ids[a] - e_lo;
       if (e < 0 || e >= E_loc) e = -1;
     }
+    const uint64_t same = same_expert_lanes(e, E_loc);
     int rank = 0;
-    uint64_t todo = __ballot(e >= 0);
-    while (todo) {
-      const int leader = __ffsll((unsigned long long)todo) - 1;
-      const int e0 = __shfl(e, leader);
-      const uint64_t m = __ballot(e == e0);
-      if (e == e0) rank = __popcll(m & lanemask_lt());
-      if (lane == leader) hist[sub * E_loc + e0] = __popcll(m);
-      todo &= ~m;
+    if (e >= 0) {
+      rank = __popcll(same & lanemask_lt());
+      if (rank == 0) hist[sub * E_loc + e] = __popcll(same);
     }
     slot[a] = e >= 0 ? (e << 6 | rank) : -1;
   }
