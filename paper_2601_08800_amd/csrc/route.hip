@@ -763,7 +763,7 @@ __global__ __launch_bounds__(1024) void route_exact_kernel(
   const int n16 = int(H * eb / 16);
   const int per = (c.E + 15) / 16;
   const int e_begin = min(c.E, wave * per), e_end = min(c.E, e_begin + per);
-  constexpr int CB = 4, U = 2;
+  constexpr int CB = 4, U = 4;   // experts per walk, pieces per lane and row in flight (8: spills)
   for (int e0 = e_begin; e0 < e_end; e0 += CB) {
     double acc[CB];
     const char* wrow[CB];

@@ -78,9 +78,10 @@ class Workload:
         return dataclasses.replace(self, **kw)
 
 
-# The six shapes of the benchmark table: tiny fp32, Qwen3-30B-A3B full layer
-# (prefill / decode), Qwen3-235B EP=8 share, DeepSeek-R1 TP=2 x 32-expert share
-# (prefill), and the same share with fp8 weights under forced Zipf routing.
+# The shapes of the benchmark table: tiny fp32, Qwen3-30B-A3B full layer
+# (prefill / decode), Qwen3-235B EP=8 share (prefill / decode), DeepSeek-R1
+# TP=2 x 32-expert share (prefill), and the same share with fp8 weights under
+# forced Zipf routing.
 CONFIGS: Dict[str, Workload] = {
     "c1": Workload("c1", 1001, T=64, H=256, E=8, k=2, I=512, act_dtype="f32",
                    weight_dtype="f32", x_std=0.02),
@@ -88,6 +89,9 @@ CONFIGS: Dict[str, Workload] = {
     "c2d": Workload("c2d", 1002, T=64, H=2048, E=128, k=8, I=768),
     "c3": Workload("c3", 1003, T=8192, H=4096, E=128, k=8, I=1536,
                    expert_lo=0, expert_hi=16, logit_bias_std=0.5),
+    # the same EP=8 share at a decode batch (256 tokens in flight)
+    "c3d": Workload("c3d", 1003, T=256, H=4096, E=128, k=8, I=1536,
+                    expert_lo=0, expert_hi=16, logit_bias_std=0.5),
     "c4": Workload("c4", 1004, T=16384, H=7168, E=256, k=8, I=2048,
                    score_fn="sigmoid", routed_scale=2.5, n_groups=8, topk_groups=4,
                    group_score_n=2, expert_lo=0, expert_hi=32, tp=2, tp_rank=0,
