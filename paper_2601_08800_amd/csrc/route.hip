@@ -192,6 +192,8 @@ __global__ __launch_bounds__(256) void gate_f64_kernel(const void* __restrict__ 
 }
 
 // ------------------------------------------ stage 1 (bf16): MFMA gate GEMM
+// Register-staged variant, used when H is not a multiple of 64 (it zero-fills
+// the K tail); otherwise gate_dma_kernel below runs the same tile.
 // Block tile 64 tokens x 128 experts, K step 64, 8 wavefronts as 2 (M) x 4 (N),
 // each one 32x32 MFMA tile (16 fp32 accumulators flushed into 16 fp64 sums every
 // K step): the flush is as much VALU work as the MFMAs are matrix work, so many
@@ -298,6 +300,162 @@ __global__ __launch_bounds__(512) void gate_mfma_kernel(const uint16_t* __restri
     const int r = m0 + lrow;
     if (lpiece == 0 && r < T) xnorm2[r] = s * 1.001f;
   }
+}
+
+// The gate GEMM with the operands brought global -> LDS directly
+// (`global_load_lds_dwordx4`, no staging registers) into a ring of NS stages:
+// one barrier per K step and an explicit vmcnt wait that leaves the younger
+// stages in flight.  Tile BM tokens x 128 experts, eight wavefronts as BM/32 (M)
+// x 256/BM (N), one or two 32x32 MFMA tiles each.  Needs H to be a multiple of 64
+// (a DMA cannot zero-fill a K tail).  LDS slot s of a stage holds (row s/8, piece
+// (s%8) ^ (row/2)&7): the lane that owns the slot fetches that piece, which is
+// the swz() layout the fragment reads expect.
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int BM, int NS, int CHAIN_STEPS>
+__device__ __forceinline__ void gate_dma_body(const uint16_t* __restrict__ x,
+                                              const uint16_t* __restrict__ gate_w, int T, int H,
+                                              int E, float* __restrict__ logits,
+                                              float* __restrict__ xnorm2, uint4* smem) {
+  constexpr int MW = BM / 32;                // wavefronts along M
+  constexpr int NT = (GBN / 32) * MW / 8;    // MFMA tiles (32 experts each) per wavefront
+  constexpr int NA = BM / 64;                // A load instructions per thread and step
+  constexpr int NLOAD = NA + 2;              // load instructions per thread and step
+  uint4* const As = smem;                    // [NS][BM * 8]
+  uint4* const Bs = smem + NS * BM * 8;      // [NS][GBN * 8]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % MW, wn = wave / MW;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * GBN;
+  const int all_steps = H / GBK;
+  const int per_split = (all_steps + gridDim.z - 1) / gridDim.z;
+  const int ks0 = blockIdx.z * per_split;
+  const int ksteps = (ks0 + per_split < all_steps ? ks0 + per_split : all_steps) - ks0;
+  logits += size_t(blockIdx.z) * T * E;
+  xnorm2 += size_t(blockIdx.z) * T;
+
+  // this thread's slots: tid + 512 i of the A stage (i < NA) and of the B stage (i < 2);
+  // rows lrow + 64 i, and (lrow + 64 i) / 2 & 7 does not depend on i
+  const int lrow = tid >> 3;
+  const int gpiece = (tid & 7) ^ ((lrow >> 1) & 7);
+  const uint16_t* asrc[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int r = m0 + lrow + 64 * i;
+    asrc[i] = x + size_t(r < T ? r : T - 1) * H + gpiece * 8;
+  }
+  const uint16_t* bsrc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int n = n0 + lrow + 64 * i;
+    bsrc[i] = gate_w + size_t(n < E ? n : E - 1) * H + gpiece * 8;
+  }
+  auto issue = [&](int ks) {
+    const int kcol = (ks0 + ks) * GBK;
+    const int st = ks % NS;
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(asrc[i] + kcol),
+                                       (lptr_t)(As + st * BM * 8 + (i * 8 + wave) * 64), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[i] + kcol),
+                                       (lptr_t)(Bs + st * GBN * 8 + (i * 8 + wave) * 64), 16, 0, 0);
+  };
+
+  f32x16 acc[NT];
+  double dsum[NT][16];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { acc[j][i] = 0.f; dsum[j][i] = 0.0; }
+  float xsq[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) xsq[i] = 0.f;
+
+#pragma unroll
+  for (int d = 0; d < NS - 1; ++d)
+    if (d < ksteps) issue(d);
+  for (int ks = 0; ks < ksteps; ++ks) {
+    // step ks must have landed; the NS-2 younger steps may stay in flight
+    if (ks + NS - 2 < ksteps) wait_vmcnt<NLOAD * (NS - 2)>(); else wait_vmcnt<0>();
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // every wavefront is done with step ks-1: refill its stage
+    if (ks + NS - 1 < ksteps) issue(ks + NS - 1);
+    const uint4* const Ast = As + (ks % NS) * BM * 8;
+    const uint4* const Bst = Bs + (ks % NS) * GBN * 8;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int piece = kk * 2 + (lane >> 5);
+      const uint4 av = Ast[swz(wm * 32 + (lane & 31), piece)];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const uint4 bv = Bst[swz((wn * NT + j) * 32 + (lane & 31), piece)];
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av),
+                                                         __builtin_bit_cast(bf16x8, bv), acc[j], 0, 0, 0);
+      }
+    }
+    if (blockIdx.y == 0) {                        // squared row norms from this thread's own pieces
+#pragma unroll
+      for (int i = 0; i < NA; ++i) {
+        const uint4 va = Ast[tid + 512 * i];
+        const uint32_t v[4] = {va.x, va.y, va.z, va.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float lo = bf16_bits_to_f32(v[q] & 0xffffu), hi = bf16_bits_to_f32(v[q] >> 16);
+          xsq[i] = fmaf(lo, lo, xsq[i]);
+          xsq[i] = fmaf(hi, hi, xsq[i]);
+        }
+      }
+    }
+    if ((ks + 1) % CHAIN_STEPS == 0 || ks + 1 == ksteps) {
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { dsum[j][i] += (double)acc[j][i]; acc[j][i] = 0.f; }
+    }
+  }
+
+  // D layout of the 32x32 MFMA: lane l, register i -> row (i/4)*8 + (l/32)*4 + i%4, col l%32
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int col = n0 + (wn * NT + j) * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = m0 + wm * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
+      if (row < T && col < E) logits[size_t(row) * E + col] = (float)dsum[j][i];
+    }
+  }
+  if (blockIdx.y == 0) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+      float s = xsq[i];
+      s += __shfl_xor(s, 1);
+      s += __shfl_xor(s, 2);
+      s += __shfl_xor(s, 4);
+      const int r = m0 + lrow + 64 * i;
+      if ((tid & 7) == 0 && r < T) xnorm2[r] = s * 1.001f;
+    }
+  }
+}
+
+template <int BM, int NS, int CHAIN_STEPS>
+__global__ __launch_bounds__(512) void gate_dma_kernel(const uint16_t* __restrict__ x,
+                                                       const uint16_t* __restrict__ gate_w, int T,
+                                                       int H, int E, float* __restrict__ logits,
+                                                       float* __restrict__ xnorm2) {
+  extern __shared__ uint4 gate_smem[];
+  // The ring is handed on as a generic pointer: with the LDS array named in the
+  // loop the compiler puts a vmcnt(0) in front of every LDS read that follows a
+  // DMA in program order, which would drain the ring; the waits and the barrier
+  // in the body order the DMA writes and the reads explicitly.
+  gate_dma_body<BM, NS, CHAIN_STEPS>(x, gate_w, T, H, E, logits, xnorm2, gate_smem);
 }
 
 // ----------------------------------------------------------- stage 2: select
@@ -910,9 +1068,19 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
       int nsplit = 1;
       while (nsplit < kGateMaxSplit && blocks * nsplit * 2 <= kGateWgTarget && ksteps / (nsplit * 2) >= 8) nsplit *= 2;
       const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN, nsplit);
-      MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(512), 0, s,
-                 static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
-                 ws.logits, ws.xnorm2);
+      if (H % GBK == 0) {
+        // two stages (48 KB): three workgroups share a CU, which measured faster than
+        // deeper rings with fewer workgroups, and than 128-token tiles
+        constexpr int NS = 2;
+        constexpr int lds = NS * (GBM + GBN) * 8 * 16;
+        MOE_LAUNCH(MOE_K_GATE_GEMM, (gate_dma_kernel<GBM, NS, kGateChainSteps>), grid, dim3(512), lds, s,
+                   static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
+                   ws.logits, ws.xnorm2);
+      } else {
+        MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(512), 0, s,
+                   static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
+                   ws.logits, ws.xnorm2);
+      }
       sc.nsplit = nsplit;
       // chains of kGateChainSteps*64 products; +2 for the flush and the store.  The
       // partial dot products of the splits obey sum_s |x_s||w_s| <= |x||w|, so the

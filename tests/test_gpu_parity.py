@@ -101,6 +101,9 @@ TILED_GATE = {
                                                         E=200, k=6, I=64),
     "softmax_bias_one_slab": gen.CONFIGS["c3"].replace(name="softmax_bias_one_slab", T=4500, H=512,
                                                        E=128, k=8, I=64, expert_lo=0, expert_hi=4),
+    # many token tiles, ragged T and E, one K slab
+    "tall_tile_ragged": gen.CONFIGS["c2p"].replace(name="tall_tile_ragged", T=8300, H=512, E=72, k=4,
+                                                   I=64),
     "sigmoid_groups_splitk": gen.CONFIGS["c4"].replace(name="sigmoid_groups_splitk", T=2100, H=1024,
                                                        E=192, k=6, I=128, n_groups=6, topk_groups=3,
                                                        expert_lo=0, expert_hi=8),
