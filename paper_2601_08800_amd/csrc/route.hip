@@ -761,9 +761,11 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     const int32_t* __restrict__ recheck) {
   __shared__ int xlist_all[4][EPL * 64];
   __shared__ double zx_all[4][EPL * 64];
+  __shared__ float2 rint_all[4][EPL * 64];     // key intervals of the listed experts
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int* const xlist = xlist_all[wave];
   double* const zx = zx_all[wave];
+  float2* const rint = rint_all[wave];
   const int n_list = counters[0];
   const size_t eb = BF16 ? 2 : 4;
 
@@ -883,10 +885,39 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     const uint32_t elig = eligible_mask<EPL>(c, kept, lane);
     Picks<float> P;
     topk_stage<float, EPL>(c, K, elig, lane, P);
-    uint32_t want = 0;
+    // Only experts whose upper bound reaches the smallest lower bound of a pick can
+    // be among the picks.  Of those, an expert whose interval is apart from every
+    // other's is ordered against all of them by its fast key already; the ones whose
+    // intervals meet another's get exact keys.
+    uint32_t region = 0;
+    float lo[EPL], hi[EPL];
 #pragma unroll
-    for (int i = 0; i < EPL; ++i)
-      if ((elig >> i & 1) && !(exact >> i & 1) && (K.key[i] + K.eps[i] >= P.low)) want |= 1u << i;
+    for (int i = 0; i < EPL; ++i) {
+      lo[i] = K.key[i] - K.eps[i];
+      hi[i] = K.key[i] + K.eps[i];
+      if ((elig >> i & 1) && hi[i] >= P.low) region |= 1u << i;
+    }
+    int nr = 0;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      const bool in = region >> i & 1;
+      const uint64_t m = __ballot(in);
+      if (in) {
+        const int pos = nr + __popcll(m & ((uint64_t(1) << lane) - 1));
+        xlist[pos] = i * 64 + lane;
+        rint[pos] = make_float2(lo[i], hi[i]);
+      }
+      nr += __popcll(m);
+    }
+    uint32_t want = 0;
+    for (int q = 0; q < nr; ++q) {
+      const int m = xlist[q];
+      const float2 iv = rint[q];
+#pragma unroll
+      for (int i = 0; i < EPL; ++i)
+        if ((region >> i & 1) && i * 64 + lane != m && lo[i] <= iv.y && iv.x <= hi[i]) want |= 1u << i;
+    }
+    want &= ~exact;
     const int n = make_list(want);
     exact_logits(t, n);
     adopt(want);
