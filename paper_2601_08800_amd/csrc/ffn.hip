@@ -720,9 +720,13 @@ __global__ __launch_bounds__(256) void ffn_skinny_kernel(
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int h = lane >> 5;
   const size_t wb = FP8 ? 1 : 2;
-  // this lane's rows: activation row, and the weight row of each of the two blocks
+  // this lane's rows: activation row, and the weight row of each of the two blocks.
+  // Lanes past the tile's last row load nothing (their fragment stays zero and
+  // their output rows are not stored): a short tile asks the memory pipeline for
+  // its real rows only.
   int ar = row0 + (lane & 31);
-  ar = ar < row1 ? ar : row1 - 1;
+  const bool a_valid = ar < row1;
+  ar = a_valid ? ar : row1 - 1;
   const uint16_t* arow = A + size_t(ar) * K + h * (W / 2);
   const char* brow[2];
 #pragma unroll
@@ -743,7 +747,8 @@ __global__ __launch_bounds__(256) void ffn_skinny_kernel(
   auto load = [&](int sl, Slice& r) {
     const int k0 = sl * W;
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) r.a[kk] = *reinterpret_cast<const uint4*>(arow + k0 + kk * 8);
+    for (int kk = 0; kk < NKK; ++kk)
+      if (a_valid) r.a[kk] = *reinterpret_cast<const uint4*>(arow + k0 + kk * 8);
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -795,6 +800,8 @@ __global__ __launch_bounds__(256) void ffn_skinny_kernel(
 
   const int nslices = K / W;
   Slice r0, r1;
+#pragma unroll
+  for (int kk = 0; kk < NKK; ++kk) r0.a[kk] = r1.a[kk] = make_uint4(0, 0, 0, 0);
   int sl = wave;
   if (sl < nslices) load(sl, r0);
   while (sl < nslices) {                     // two slices per trip: r0 and r1 alternate
