@@ -1072,7 +1072,8 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   const int epl = (E + 63) / 64;
   // decode-sized batches: the exact gate costs T*E*H fp64 fused multiply-adds, a
   // few microseconds up to about 2^28 of them: one kernel does the whole stage
-  const bool small = size_t(T) * E * H <= (size_t(1) << 28);
+  // (a workgroup per token: not for long batches of tiny layers)
+  const bool small = size_t(T) * E * H <= (size_t(1) << 28) && T <= 4096;
   if (!logits_in && small) {
     if (epl <= 1) launch_route_exact<1>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
     else if (epl <= 2) launch_route_exact<2>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);

@@ -92,7 +92,8 @@ def test_route_recheck_counter_and_determinism():
     assert np.array_equal(a[0], host(L.topk_ids)) and np.array_equal(a[1], host(L.topk_w))
 
 
-# Token counts past the decode-size threshold of the router (T*E*H > 2^28), so the
+# Token counts past the decode-size threshold of the router (T*E*H > 2^28, or more
+# than 4096 tokens), so the
 # tiled bf16 gate GEMM, the interval test and the fp64 re-scoring run, at sizes
 # the oracle still scores in seconds: ragged T / E / H tails, with and without a
 # split K range, soft-max with a logit bias and sigmoid with a group limit.
@@ -104,6 +105,9 @@ TILED_GATE = {
     # many token tiles, ragged T and E, one K slab
     "tall_tile_ragged": gen.CONFIGS["c2p"].replace(name="tall_tile_ragged", T=8300, H=512, E=72, k=4,
                                                    I=64),
+    # fp32 activations past the one-kernel route: fp64 VALU gate, then select / re-score
+    "f32_many_tokens": gen.CONFIGS["c1"].replace(name="f32_many_tokens", T=4200, H=256, E=16, k=2,
+                                                 I=64),
     "sigmoid_groups_splitk": gen.CONFIGS["c4"].replace(name="sigmoid_groups_splitk", T=2100, H=1024,
                                                        E=192, k=6, I=128, n_groups=6, topk_groups=3,
                                                        expert_lo=0, expert_hi=8),
@@ -113,7 +117,7 @@ TILED_GATE = {
 @pytest.mark.parametrize("name", list(TILED_GATE))
 def test_route_tiled_gate_matches_oracle(name):
     w = TILED_GATE[name]
-    assert w.T * w.E * w.H > 2 ** 28
+    assert w.T * w.E * w.H > 2 ** 28 or w.T > 4096
     print("case", name, flush=True)
     d = inputs(w)
     L = make_layer(w, d)
