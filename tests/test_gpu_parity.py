@@ -283,3 +283,40 @@ def test_ffn_degenerate_loads(counts):
     for t in rows:
         one, _ = oracle.layer_share(d["x"][t:t + 1], ids[t:t + 1], tw[t:t + 1], 0, w.E, d["experts"])
         assert rel_err(out[t:t + 1], one) <= TOL["bf16"]
+
+
+def _random_workload(seed):
+    """A small layer with seeded random shape and gate options (every size a legal
+    but awkward one: odd expert counts, k up to 8, ragged token counts, EP ranges)."""
+    rng = np.random.default_rng(1000 + seed)
+    score = "sigmoid" if rng.random() < 0.5 else "softmax"
+    G = 1
+    E = int(rng.integers(2, 200))
+    if score == "sigmoid" and rng.random() < 0.6:
+        G = int(rng.choice([2, 3, 4, 8]))
+        E = G * int(rng.integers(2, 24))
+    gs = E // G
+    Kg = int(rng.integers(1, G + 1)) if G > 1 else 1
+    gn = int(rng.integers(1, min(gs, 3) + 1)) if G > 1 else 0
+    k = int(rng.integers(1, min(8, Kg * gs if G > 1 else E) + 1))
+    lo = int(rng.integers(0, E))
+    hi = int(rng.integers(lo + 1, E + 1))
+    return gen.CONFIGS["c2p"].replace(
+        name="random_%d" % seed, seed=5000 + seed, T=int(rng.integers(1, 400)),
+        H=8 * int(rng.integers(8, 64)), E=E, k=k, I=8 * int(rng.integers(4, 24)), score_fn=score,
+        renormalize=bool(rng.random() < 0.7), routed_scale=float(rng.choice([1.0, 2.5])),
+        n_groups=G, topk_groups=Kg, group_score_n=gn, expert_lo=lo, expert_hi=hi,
+        logit_bias_std=float(rng.choice([0.0, 0.5])),
+        select_bias_std=0.05 if score == "sigmoid" else 0.0)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_small_layers(seed):
+    w = _random_workload(seed)
+    print("case", w, flush=True)
+    d, L, out = run_full(w)
+    ids_ref, w_ref, margin = oracle_route(w, d["x"], d["gate"])
+    check_routing(host(L.topk_ids), host(L.topk_w), ids_ref, w_ref, margin, w.routed_scale, w.name)
+    check_dispatch(L, ids_ref, w, d["x"])
+    ref, _ = oracle.layer_share(d["x"], ids_ref, w_ref, w.expert_lo, w.e_hi, d["experts"], d["shared"])
+    assert rel_err(out, ref) <= TOL["bf16"] or np.abs(ref).max() == 0
