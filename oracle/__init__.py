@@ -155,8 +155,8 @@ def combine(ys, inv, w, shared_ys=None):
     ys = np.ascontiguousarray(ys, np.float64)
     w = np.ascontiguousarray(w, np.float32)
     T, k = w.shape
-    H = ys.shape[1] if ys.size else (shared_ys.shape[1] if shared_ys is not None else 0)
-    if ys.size == 0:
+    H = ys.shape[1]
+    if ys.shape[0] == 0:
         ys = np.zeros((1, H), np.float64)
     inv = np.ascontiguousarray(inv, np.int32).reshape(T * k)
     sh = None if shared_ys is None else np.ascontiguousarray(shared_ys, np.float64)

@@ -175,6 +175,24 @@ def test_combine_weighted_gather():
     np.testing.assert_allclose(out2, 2 * oracle.combine(ys, inv, w, None), rtol=1e-6)
     out3 = oracle.combine(ys, np.full(T * k, -1, np.int32), w, sh)
     assert np.array_equal(out3, sh.astype(np.float32))
+    # a rank that received no row at all (an empty buffer of the right width): the
+    # sum over no experts is zero, with the layer's full shape
+    none = oracle.combine(np.zeros((0, H)), np.full(T * k, -1, np.int32), w, None)
+    assert none.shape == (T, H) and not none.any()
+
+
+def test_layer_share_with_no_local_assignment():
+    rng = np.random.default_rng(21)
+    T, H, E, k, I = 9, 16, 12, 3, 8
+    x = rng.standard_normal((T, H)).astype(np.float32)
+    ids = rng.integers(0, 5, (T, k)).astype(np.int32)          # nothing goes to experts 7..8
+    w = rng.random((T, k)).astype(np.float32)
+    ex = {"w_gate": rng.standard_normal((2, I, H)).astype(np.float32),
+          "w_up": rng.standard_normal((2, I, H)).astype(np.float32),
+          "w_down": rng.standard_normal((2, H, I)).astype(np.float32)}
+    out, parts = oracle.layer_share(x, ids, w, 7, 9, ex)
+    assert out.shape == (T, H) and not out.any()
+    assert parts["counts"].tolist() == [0, 0] and (parts["inv"] == -1).all()
 
 
 def test_identity_experts_return_input():
