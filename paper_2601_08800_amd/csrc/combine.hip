@@ -53,7 +53,9 @@ __global__ __launch_bounds__(256) void combine_bf16_kernel(
   }
   const uint64_t have = __ballot(pos >= 0);
   constexpr int P = 4;                          // pieces per lane in flight
-  for (int c0 = lane; c0 < row8; c0 += 64 * P) {
+  // the loop bounds are the same in every lane (the shuffles below need all of them)
+  for (int cb = 0; cb < row8; cb += 64 * P) {
+    const int c0 = cb + lane;
     float acc[P][8];
 #pragma unroll
     for (int i = 0; i < P; ++i)
@@ -118,7 +120,10 @@ __global__ __launch_bounds__(256) void combine_f32_kernel(
     wt = w[size_t(t) * k + lane];
   }
   const uint64_t have = __ballot(pos >= 0);
-  for (int c = lane; c < row4; c += 64) {
+  // the loop bounds are the same in every lane (the shuffles below need all of them)
+  for (int cb = 0; cb < row4; cb += 64) {
+    const int c = cb + lane;
+    const bool in = c < row4;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     uint64_t m = have;
     while (m) {
@@ -126,12 +131,15 @@ __global__ __launch_bounds__(256) void combine_f32_kernel(
       m &= m - 1;
       const int p = __shfl(pos, j);
       const float wj = __shfl(wt, j);
-      const float4 v = ys[size_t(p) * row4 + c];
-      acc.x = fmaf(wj, v.x, acc.x);
-      acc.y = fmaf(wj, v.y, acc.y);
-      acc.z = fmaf(wj, v.z, acc.z);
-      acc.w = fmaf(wj, v.w, acc.w);
+      if (in) {
+        const float4 v = ys[size_t(p) * row4 + c];
+        acc.x = fmaf(wj, v.x, acc.x);
+        acc.y = fmaf(wj, v.y, acc.y);
+        acc.z = fmaf(wj, v.z, acc.z);
+        acc.w = fmaf(wj, v.w, acc.w);
+      }
     }
+    if (!in) continue;
     if (shared_ys) {
       const float4 v = shared_ys[size_t(t) * row4 + c];
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;

@@ -41,6 +41,12 @@ SMALL = {
     # many experts per lane slot and a large k
     "wide_gate": gen.CONFIGS["c2p"].replace(name="wide_gate", T=150, H=256, E=512, k=16, I=64,
                                             expert_lo=100, expert_hi=400),
+    # rows shorter than a wavefront's 64 pieces, and rows whose last pieces are a second,
+    # partly filled pass of the wavefront (the combine walks a row in 64-piece steps)
+    "hidden_8": gen.CONFIGS["c2p"].replace(name="hidden_8", T=40, H=8, E=16, k=3, I=704, tp=2,
+                                           shared_expert=True, expert_lo=10, expert_hi=12),
+    "f32_hidden_264": gen.CONFIGS["c1"].replace(name="f32_hidden_264", T=2500, H=264, E=32, k=3,
+                                                I=80, tp=2, expert_lo=30, expert_hi=31),
     # fp8 weights, natural routing
     "fp8_small": gen.CONFIGS["c5"].replace(name="fp8_small", T=300, H=512, E=64, k=8, I=512,
                                            expert_lo=0, expert_hi=8, zipf_s=None),
