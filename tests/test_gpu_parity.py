@@ -326,3 +326,55 @@ def test_random_small_layers(seed):
     check_dispatch(L, ids_ref, w, d["x"])
     ref, _ = oracle.layer_share(d["x"], ids_ref, w_ref, w.expert_lo, w.e_hi, d["experts"], d["shared"])
     assert rel_err(out, ref) <= TOL["bf16"] or np.abs(ref).max() == 0
+
+
+def _random_ffn_workload(seed):
+    """Seeded random layers that vary what the expert FFN sees: activation / weight
+    dtype, shared expert, TP slice, sizes that reach every GEMM family (hidden and
+    intermediate sizes that are multiples of 8, 64 or 128; 3 to 2500 tokens)."""
+    r = np.random.default_rng(7000 + seed)
+    kind = r.choice(["bf16", "fp8", "f32"], p=[0.5, 0.35, 0.15])
+    E = int(r.choice([4, 8, 16, 32]))
+    k = int(r.integers(1, min(4, E) + 1))
+    mult = 128 if kind == "fp8" else (64 if r.random() < 0.5 else 8)
+    H = mult * int(r.integers(1, max(2, 1024 // mult)))
+    tp = int(r.choice([1, 2]))
+    I = tp * mult * int(r.integers(1, max(2, 512 // mult)))
+    Tn = int(r.choice([3, 40, 200, 900, 2500]))
+    lo = int(r.integers(0, E))
+    hi = int(r.integers(lo + 1, E + 1))
+    base = gen.CONFIGS["c1"] if kind == "f32" else gen.CONFIGS["c2p"]
+    return base.replace(name="random_ffn_%d" % seed, seed=9000 + seed, T=Tn, H=H, E=E, k=k, I=I,
+                        expert_lo=lo, expert_hi=hi, tp=tp, tp_rank=int(r.integers(0, tp)),
+                        shared_expert=bool(r.random() < 0.4), weight_dtype=str(kind))
+
+
+# 118 and 183 once exposed the combine's handling of rows shorter than 64 pieces
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 4, 5, 6, 7, 9, 11, 118, 183])
+def test_random_ffn_families(seed):
+    w = _random_ffn_workload(seed)
+    print("case", w, flush=True)
+    d, L, out = run_full(w)
+    ids_ref, w_ref, margin = oracle_route(w, d["x"], d["gate"])
+    check_routing(host(L.topk_ids), host(L.topk_w), ids_ref, w_ref, margin, w.routed_scale, w.name)
+    check_dispatch(L, ids_ref, w, d["x"])
+    ref, _ = oracle.layer_share(d["x"], ids_ref, w_ref, w.expert_lo, w.e_hi, d["experts"], d["shared"])
+    err = rel_err(out, ref) if np.abs(ref).max() > 0 else float(np.abs(out).max())
+    assert err <= TOL[w.weight_dtype], err
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_routing_past_4096_tokens(seed):
+    """The random gate options of `_random_workload` at 4097..7000 tokens: tiled
+    gate GEMM (or the fp64 gate for fp32 inputs), interval test, re-scoring."""
+    r = np.random.default_rng(33000 + seed)
+    w = _random_workload(seed).replace(T=int(r.integers(4097, 7000)), I=8, name="random_route_%d" % seed)
+    if r.random() >= 0.8:
+        w = w.replace(act_dtype="f32", weight_dtype="f32")
+    print("case", w, flush=True)
+    d = inputs(w)
+    L = make_layer(w, d)
+    L.route(dev(d["x"]))
+    torch.cuda.synchronize()
+    ids_ref, w_ref, margin = oracle_route(w, d["x"], d["gate"])
+    check_routing(host(L.topk_ids), host(L.topk_w), ids_ref, w_ref, margin, w.routed_scale, w.name)
