@@ -144,3 +144,25 @@ def test_shard_and_stage_full_size(name, m, n_nodes):
     rows = np.unique(np.concatenate([np.arange(64), np.arange(w.T - 64, w.T),
                                      np.random.default_rng(2).integers(0, w.T, 256)]))
     run_case(w, m, n_nodes, ids, tw, [0, m - 1], sample_rows=rows)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_shard_and_stage(seed):
+    """Seeded random shapes: 1..8 TP ranks, shard rows from 8 elements up, 1..4 source
+    nodes, bf16 and fp32 activations, EP sub-ranges."""
+    r = np.random.default_rng(51000 + seed)
+    f32 = r.random() < 0.25
+    m = int(r.choice([1, 2, 4, 8]))
+    H = m * 8 * int(r.integers(1, 40))
+    E = int(r.integers(2, 80))
+    k = int(r.integers(1, min(8, E) + 1))
+    lo = int(r.integers(0, E))
+    hi = int(r.integers(lo + 1, E + 1))
+    n_nodes = int(r.integers(1, min(4, hi - lo) + 1))
+    base = gen.CONFIGS["c1"] if f32 else gen.CONFIGS["c2p"]
+    w = base.replace(name="random_stage_%d" % seed, seed=12000 + seed, T=int(r.integers(1, 500)), H=H,
+                     E=E, k=k, I=8, expert_lo=lo, expert_hi=hi)
+    print("case", w, "ranks", m, "nodes", n_nodes, flush=True)
+    d = inputs(w)
+    ids, tw, _ = oracle_route(w, d["x"], d["gate"])
+    run_case(w, m, n_nodes, ids, tw, range(m))
