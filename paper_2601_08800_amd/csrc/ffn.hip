@@ -923,14 +923,9 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
   auto k1 = ffn_gemm_kernel<BM, BN1, WM, WN1, true, FP8>;
   auto k2 = ffn_gemm_kernel<BM, BN2, WM, WN2, false, FP8>;
   constexpr int lds1 = 2 * (BM + 2 * BN1) * 8 * 16, lds2 = 2 * (BM + BN2) * 8 * 16;
-  static bool configured = false;   // LDS above 64 KB must be opted into, once per kernel
-  if (!configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, lds1);
-    hipFuncSetAttribute(reinterpret_cast<const void*>(k2),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, lds2);
-    configured = true;
-  }
+  static uint64_t opted1 = 0, opted2 = 0;
+  lds_opt_in(reinterpret_cast<const void*>(k1), lds1, opted1);
+  lds_opt_in(reinterpret_cast<const void*>(k2), lds2, opted2);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(size_t(max_mt) * nt1), dim3(256), lds1, s,
                      static_cast<const uint16_t*>(xs), w_gate, w_up, s_gate, s_up,
                      static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
@@ -980,14 +975,9 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt2 * nt2 + 7) / 8 * 8;
   auto k1 = ffn_gemm8w_kernel<true>;
   auto k2 = ffn_gemm8w_kernel<false>;
-  static bool configured = false;     // LDS above 64 KB must be opted into, once per kernel
-  if (!configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(k1),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    hipFuncSetAttribute(reinterpret_cast<const void*>(k2),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    configured = true;
-  }
+  static uint64_t opted1 = 0, opted2 = 0;
+  lds_opt_in(reinterpret_cast<const void*>(k1), lds, opted1);
+  lds_opt_in(reinterpret_cast<const void*>(k2), lds, opted2);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
              static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
              static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);

@@ -63,6 +63,18 @@ extern bool g_prof_on;
     if (::moe::g_prof_on) ::moe::prof_mark(id, stream, false);           \
   } while (0)
 
+// A kernel that uses more than 64 KB of dynamic LDS must opt in, once per device.
+// `done` is the call site's own record (one bit per device ordinal); a repeated
+// call from a racing thread is harmless.
+inline void lds_opt_in(const void* kernel, int bytes, uint64_t& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return;
+  const uint64_t bit = uint64_t(1) << (dev & 63);
+  if (done & bit) return;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess)
+    done |= bit;
+}
+
 // ---- launchers (return hipGetLastError() of their launches) ---------------
 hipError_t launch_route(const moe_config& c, int T, const void* x, const void* gate_w,
                         const float* logit_bias, const float* select_bias,
