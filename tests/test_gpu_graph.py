@@ -13,8 +13,12 @@ pytestmark = pytest.mark.gpu
 CASES = {
     # decode-sized full layer: launch-bound, the case graphs are for
     "decode": gen.CONFIGS["c2d"].replace(name="graph_decode", T=64, H=512, E=32, k=4, I=256),
-    # prefill-sized groups (256-row kernel, fp64 re-scoring list in use)
+    # prefill-sized groups (256-row kernel)
     "prefill": gen.CONFIGS["c2p"].replace(name="graph_prefill", T=1024, H=512, E=8, k=2, I=256),
+    # enough tokens for the tiled gate GEMM, the interval test with its re-scoring list
+    # (a counter cleared by a kernel inside the graph) and the multi-kernel dispatch
+    "tiled_route": gen.CONFIGS["c3"].replace(name="graph_tiled", T=4500, H=512, E=128, k=8, I=64,
+                                             expert_lo=0, expert_hi=4),
     # shared expert on its second stream inside the capture, sigmoid grouped routing
     "shared": gen.CONFIGS["c4"].replace(name="graph_shared", T=300, H=512, E=64, k=8, I=256,
                                         expert_lo=0, expert_hi=16),
