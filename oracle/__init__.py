@@ -150,6 +150,36 @@ def expert_ffn(offsets, xs, w_gate, w_up, w_down, s_gate=None, s_up=None, s_down
     return ys
 
 
+def quant_act_1x128(x):
+    """On-the-fly activation quantisation, one scale per row and 128 columns.
+    Returns (codes uint8 [rows,K], scales float32 [rows,K/128])."""
+    x = decode(x)
+    rows, K = x.shape
+    assert K % 128 == 0
+    codes = np.empty((rows, K), np.uint8)
+    scales = np.empty((rows, K // 128), np.float32)
+    _load().oracle_quant_act_1x128(rows, K, _p(x), _p(codes), _p(scales))
+    return codes, scales
+
+
+def expert_ffn_fp8act(offsets, xs, w_gate, w_up, w_down, s_gate, s_up, s_down):
+    """The grouped SwiGLU MLP with activations quantised 1x128 on the fly (input
+    rows, and the bf16-stored intermediate) and block-scaled e4m3 weights.
+    Returns ys float64."""
+    offsets = np.ascontiguousarray(offsets, np.int32)
+    xs = decode(xs)
+    wg, wu, wd = decode(w_gate), decode(w_up), decode(w_down)
+    n, I, H = wg.shape
+    assert H % 128 == 0 and I % 128 == 0
+    assert wu.shape == (n, I, H) and wd.shape == (n, H, I) and offsets.shape == (n + 1,)
+    assert xs.shape[1] == H and xs.shape[0] >= offsets[-1]
+    sc = [np.ascontiguousarray(s, np.float32) for s in (s_gate, s_up, s_down)]
+    ys = np.zeros((xs.shape[0], H), np.float64)
+    _load().oracle_expert_ffn_fp8act(n, _p(offsets), H, I, _p(xs), _p(wg), _p(wu), _p(wd),
+                                     _p(sc[0]), _p(sc[1]), _p(sc[2]), _p(ys))
+    return ys
+
+
 def combine(ys, inv, w, shared_ys=None):
     """Gate-weighted return along the route.  Returns out float32 [T,H]."""
     ys = np.ascontiguousarray(ys, np.float64)

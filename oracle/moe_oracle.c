@@ -243,6 +243,113 @@ void oracle_expert_ffn(int n_experts, const int32_t *offsets, int H, int I,
     }
 }
 
+/* ---- expert MLP with 8-bit activations (scope extension, not in the paper) -- */
+/*
+ * Activations are quantised on the fly, one fp32 scale per row and block of
+ * 128 columns: amax = max|x| over the block, scale = amax / 448 (1 when the
+ * block is all zero), code = e4m3(x / scale) with round-to-nearest-even after
+ * clamping to +-448.  amax, the two divisions and the clamp are fp32 operations
+ * (the decision which code a value gets is taken in fp32 on both sides); the
+ * value a code stands for, decode(code) * scale, and every sum are fp64.
+ */
+static double e4m3_value(int c)
+{
+    int ex = (c >> 3) & 15, m = c & 7;
+    double v = ex == 0 ? ldexp((double)m / 8.0, -6) : ldexp(1.0 + (double)m / 8.0, ex - 7);
+    return (c & 0x80) ? -v : v;
+}
+
+/* nearest finite e4m3 value, ties to the even code: a search over all codes */
+static uint8_t e4m3_nearest(float q)
+{
+    int best = 0;
+    double bd = fabs((double)q);
+    for (int c = 1; c < 0x7F; ++c) {
+        double d = fabs(fabs((double)q) - e4m3_value(c));
+        if (d < bd || (d == bd && (c & 1) == 0 && (best & 1) == 1)) { bd = d; best = c; }
+    }
+    return (uint8_t)(best | (signbit(q) ? 0x80 : 0));
+}
+
+/* x [rows,K] fp32, K a multiple of 128 -> codes [rows,K], scales [rows,K/128] */
+void oracle_quant_act_1x128(int rows, int K, const float *x, uint8_t *codes, float *scales)
+{
+    int nb = K / 128;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < rows; ++r)
+        for (int b = 0; b < nb; ++b) {
+            const float *xb = x + (size_t)r * K + (size_t)b * 128;
+            float amax = 0.0f;
+            for (int j = 0; j < 128; ++j) amax = fmaxf(amax, fabsf(xb[j]));
+            float scale = amax > 0.0f ? amax / 448.0f : 1.0f;
+            scales[(size_t)r * nb + b] = scale;
+            for (int j = 0; j < 128; ++j) {
+                float q = xb[j] / scale;
+                q = fminf(fmaxf(q, -448.0f), 448.0f);
+                codes[(size_t)r * K + (size_t)b * 128 + j] = e4m3_nearest(q);
+            }
+        }
+}
+
+static float round_to_bf16(double v)
+{
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);      /* round to nearest even on the upper half */
+    u &= 0xFFFF0000u;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/*
+ * The grouped SwiGLU MLP of oracle_expert_ffn with quantised activations:
+ *   xq = quant(xs row);  g = Wgate_e xq, u = Wup_e xq;  hmid = g*sigmoid(g)*u
+ *   stored as bf16, then quantised the same way;  ys_r = Wdown_e hq.
+ * Weights are e4m3 values (already decoded to fp32) with 128x128 block scales.
+ * H and I are multiples of 128.  ys [rows,H] fp64.
+ */
+void oracle_expert_ffn_fp8act(int n_experts, const int32_t *offsets, int H, int I,
+                              const float *xs, const float *w_gate, const float *w_up,
+                              const float *w_down, const float *s_gate, const float *s_up,
+                              const float *s_down, double *ys)
+{
+    int bH = H / 128, bI = I / 128;
+    for (int e = 0; e < n_experts; ++e) {
+        const float *Wg = w_gate + (size_t)e * I * H;
+        const float *Wu = w_up + (size_t)e * I * H;
+        const float *Wd = w_down + (size_t)e * H * I;
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int r = offsets[e]; r < offsets[e + 1]; ++r) {
+            uint8_t *cx = (uint8_t *)malloc((size_t)H), *ch = (uint8_t *)malloc((size_t)I);
+            float *sx = (float *)malloc(sizeof(float) * bH), *sh = (float *)malloc(sizeof(float) * bI);
+            float *hb = (float *)malloc(sizeof(float) * I);
+            double *xq = (double *)malloc(sizeof(double) * H), *hq = (double *)malloc(sizeof(double) * I);
+            oracle_quant_act_1x128(1, H, xs + (size_t)r * H, cx, sx);
+            for (int h = 0; h < H; ++h) xq[h] = e4m3_value(cx[h]) * (double)sx[h / 128];
+            for (int i = 0; i < I; ++i) {
+                double g = 0.0, u = 0.0;
+                for (int h = 0; h < H; ++h) {
+                    double wg = (double)Wg[(size_t)i * H + h] * (double)s_gate[((size_t)e * bI + i / 128) * bH + h / 128];
+                    double wu = (double)Wu[(size_t)i * H + h] * (double)s_up[((size_t)e * bI + i / 128) * bH + h / 128];
+                    g += wg * xq[h];
+                    u += wu * xq[h];
+                }
+                hb[i] = round_to_bf16(g / (1.0 + exp(-g)) * u);
+            }
+            oracle_quant_act_1x128(1, I, hb, ch, sh);
+            for (int i = 0; i < I; ++i) hq[i] = e4m3_value(ch[i]) * (double)sh[i / 128];
+            for (int h = 0; h < H; ++h) {
+                double acc = 0.0;
+                for (int i = 0; i < I; ++i)
+                    acc += (double)Wd[(size_t)h * I + i] * (double)s_down[((size_t)e * bH + h / 128) * bI + i / 128] * hq[i];
+                ys[(size_t)r * H + h] = acc;
+            }
+            free(cx); free(ch); free(sx); free(sh); free(hb); free(xq); free(hq);
+        }
+    }
+}
+
 /* ---- combine: weighted return along the route (Alg. 1; Sec. III-B-2 AR) -- */
 /*
  * out[t,:] = sum over j ascending with inv[t*k+j] >= 0 of
