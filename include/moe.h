@@ -233,6 +233,27 @@ moe_status moe_profile_filter(uint32_t mask);
  * MOE_K_COUNT entries), and clears the records (recording stays enabled). */
 moe_status moe_profile_read(double* total_ms, int32_t* launches);
 
+/* ---- expert FFN with 8-bit activations (an extension beyond the paper: both
+ * GEMM operands e4m3, fp8 matrix instructions) --------------------------------
+ * Same arguments and semantics as moe_expert_ffn for cfg->act_dtype = MOE_BF16,
+ * cfg->weight_dtype = MOE_FP8_E4M3_B128, hidden and inter_local multiples of
+ * 128 (otherwise MOE_ERR_UNSUPPORTED), except for the arithmetic: every input
+ * row is quantised on the fly, one fp32 scale per row and block of 128 columns
+ * (scale = max|x| / 448, 1 for an all-zero block; code = e4m3(x / scale),
+ * round to nearest even after a clamp to +-448; fp32 operations), the products
+ * of a 128-deep K block are summed in fp32 and multiplied by the row's and the
+ * weight block's scales, and the SwiGLU intermediate, stored as bf16 in the
+ * workspace, is quantised the same way before the down projection.  ys is bf16.
+ * Workspace: moe_fp8act_workspace_bytes(cfg, n_experts_here, rows_capacity)
+ * bytes (0 for an unsupported configuration). */
+size_t moe_fp8act_workspace_bytes(const moe_config* cfg, int32_t n_experts_here,
+                                  int32_t rows_capacity);
+moe_status moe_expert_ffn_fp8act(const moe_config* cfg, int32_t n_experts_here, const void* xs,
+                                 const int32_t* offsets, int32_t rows_capacity, const void* w_gate,
+                                 const void* w_up, const void* w_down, const float* s_gate,
+                                 const float* s_up, const float* s_down, void* ys, void* ws,
+                                 size_t ws_bytes, void* stream);
+
 /* Static name of a kernel id (host pointer). */
 const char* moe_kernel_name(int32_t id);
 

@@ -15,6 +15,7 @@ _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatch",
            "moe_dispatch_shard", "moe_expert_ffn", "moe_combine", "moe_combine_stage",
+           "moe_fp8act_workspace_bytes", "moe_expert_ffn_fp8act",
            "moe_profile_enable", "moe_profile_read",
            "moe_profile_filter",
            "moe_kernel_name")
@@ -71,6 +72,10 @@ def load_library():
         lib.moe_combine_stage.argtypes = [cfgp, i32, vp, vp, vp, i32, i32, vp, vp]
         lib.moe_expert_ffn.restype = ctypes.c_int
         lib.moe_expert_ffn.argtypes = [cfgp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_expert_ffn_fp8act.restype = ctypes.c_int
+        lib.moe_expert_ffn_fp8act.argtypes = [cfgp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_fp8act_workspace_bytes.restype = sz
+        lib.moe_fp8act_workspace_bytes.argtypes = [cfgp, i32, i32]
         lib.moe_combine.restype = ctypes.c_int
         lib.moe_combine.argtypes = [cfgp, i32, vp, vp, vp, vp, vp, vp]
         lib.moe_profile_enable.restype = ctypes.c_int
@@ -156,6 +161,19 @@ def moe_expert_ffn(cfg, n_experts_here, xs, offsets, rows_capacity, w_gate, w_up
                                        _ws_bytes(ws) if ws_bytes is None else ws_bytes,
                                        _stream(stream))
     _check(st, "moe_expert_ffn")
+
+
+def moe_fp8act_workspace_bytes(cfg: MoEConfig, n_experts_here: int, rows_capacity: int) -> int:
+    return int(load_library().moe_fp8act_workspace_bytes(ctypes.byref(cfg), n_experts_here, rows_capacity))
+
+
+def moe_expert_ffn_fp8act(cfg, n_experts_here, xs, offsets, rows_capacity, w_gate, w_up, w_down,
+                          s_gate, s_up, s_down, ys, ws, stream=None, ws_bytes=None):
+    st = load_library().moe_expert_ffn_fp8act(
+        ctypes.byref(cfg), n_experts_here, _ptr(xs), _ptr(offsets), rows_capacity, _ptr(w_gate),
+        _ptr(w_up), _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(ys), _ptr(ws),
+        _ws_bytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    _check(st, "moe_expert_ffn_fp8act")
 
 
 def moe_combine(cfg, T, ys, inv, topk_w, shared_ys, out, stream=None):

@@ -23,7 +23,7 @@ def cfg(**kw):
 
 def test_header_symbols_are_exported():
     hdr = open(os.path.join(ROOT, "include", "moe.h")).read()
-    declared = set(re.findall(r"\b(moe_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(B.EXPORTS)
     lib = ctypes.CDLL(moe.lib_path())
     for name in declared:
