@@ -14,8 +14,8 @@
 //
 // GEMM tile: 128 rows x 128 weight rows (DUAL: 64 gate + the matching 64 up
 // rows), K step 128 bytes = one scale block, 256 threads = 4 wavefronts as 2 (M)
-// x 2 (N), each 2 x 2 MFMA tiles.  Operands go global -> registers -> LDS (two
-// stages), rows of 128 bytes with the piece index XOR-ed by (row/2)&7.  Inside a
+// x 2 (N), each 2 x 2 MFMA tiles.  Operands go global -> LDS by DMA (two stages),
+// rows of 128 bytes with the piece index XOR-ed by (row/2)&7.  Inside a
 // K step, MFMA sub-step s of lane half h takes bytes (2s+h)*32 .. +32 of the row
 // for BOTH operands, so the pairing of A and B elements is right whatever order
 // the instruction walks K in.
@@ -108,16 +108,23 @@ __global__ __launch_bounds__(512) void fp8act_tiles_kernel(const int32_t* __rest
 // ------------------------------------------------------------------- GEMM
 // A codes [rows, K], sA_t [K/128][rows_capacity]; B codes [n_experts][N][K] (DUAL:
 // B0 = gate, B1 = up), S [n_experts][N/128][K/128]; C bf16 [rows, N].
+// Operands go global -> LDS directly (`global_load_lds_dwordx4`) into two
+// stages: the loads of step k+1 are issued right after the barrier of step k and
+// waited for before the barrier of step k+1; two workgroups share a CU and fill
+// each other's waits.  LDS slot s of a stage holds (row s/8, piece (s%8) ^
+// (row/2)&7); the lane that owns the slot fetches that piece.
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
 template <bool DUAL>
-__global__ __launch_bounds__(256) void fp8act_gemm_kernel(
+__device__ __forceinline__ void fp8act_gemm_body(
     const uint8_t* __restrict__ A, const float* __restrict__ sA_t, int rows_capacity,
     const uint8_t* __restrict__ B0, const uint8_t* __restrict__ B1, const float* __restrict__ S0,
     const float* __restrict__ S1, uint16_t* __restrict__ C, int N, int K,
-    const int32_t* __restrict__ tiles) {
-  extern __shared__ uint4 fsmem[];
-  uint4* const As = fsmem;                        // [2][FBM * 8]
-  uint4* const Bs = fsmem + 2 * FBM * 8;          // [2][FBN * 8]
-  float* const Ss = reinterpret_cast<float*>(fsmem + 2 * FBM * 8 + 2 * FBN * 8);   // [2][FBM]
+    const int32_t* __restrict__ tiles, uint4* smem) {
+  uint4* const As = smem;                         // [2][FBM * 8]
+  uint4* const Bs = smem + 2 * FBM * 8;           // [2][FBN * 8]
+  float* const Ss = reinterpret_cast<float*>(smem + 2 * FBM * 8 + 2 * FBN * 8);   // [2][FBM]
   constexpr int CN = DUAL ? 64 : 128;             // output columns per workgroup
   const int n_ntiles = N / CN;
   const int mtile = blockIdx.x / n_ntiles, ntile = blockIdx.x % n_ntiles;
@@ -130,41 +137,38 @@ __global__ __launch_bounds__(256) void fp8act_gemm_kernel(
   const int h = lane >> 5, l31 = lane & 31;
   const int nkb = K / kQBlock, nnb = N / 128;
 
-  // staging: thread owns pieces (row = lrow + 32 i, piece = tid & 7), i < 4, of A and of B
-  const int lrow = tid >> 3, lpiece = tid & 7;
+  // this thread's slots: tid + 256 i (i < 4) of the A stage and of the B stage: rows
+  // (tid >> 3) + 32 i, and (row / 2) & 7 does not depend on i
+  const int lrow = tid >> 3;
+  const int gpiece = (tid & 7) ^ ((lrow >> 1) & 7);
   const uint8_t* ap[4];
   const uint8_t* bp[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     int r = row0 + lrow + 32 * i;
     r = r < row1 ? r : row1 - 1;
-    ap[i] = A + size_t(r) * K + lpiece * 16;
+    ap[i] = A + size_t(r) * K + gpiece * 16;
     const int br = lrow + 32 * i;                 // row of the B tile: DUAL 0..63 gate, 64..127 up
     const uint8_t* base = (DUAL && br >= 64) ? B1 : B0;
     const int n = n0 + ((DUAL && br >= 64) ? br - 64 : br);
-    bp[i] = base + (size_t(e) * N + n) * K + lpiece * 16;
+    bp[i] = base + (size_t(e) * N + n) * K + gpiece * 16;
   }
-  const int srow = row0 + (tid & 127) < row1 ? row0 + (tid & 127) : row1 - 1;   // scale staging (tid < 128)
+  const int srow = row0 + (tid & 127) < row1 ? row0 + (tid & 127) : row1 - 1;
   const float* s0p = S0 + (size_t(e) * nnb + n0 / 128) * nkb;
   const float* s1p = DUAL ? S1 + (size_t(e) * nnb + n0 / 128) * nkb : nullptr;
 
-  uint4 ra[4], rb[4];
-  float rs = 0.f;
-  auto gload = [&](int kb) {
+  float rs;                                       // this thread's row scale of the step in flight
+  auto issue = [&](int kb) {
+    const int st = kb & 1;
+    rs = sA_t[size_t(kb) * rows_capacity + srow];          // first: the oldest load of the group
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ra[i] = *reinterpret_cast<const uint4*>(ap[i] + size_t(kb) * kQBlock);
-      rb[i] = *reinterpret_cast<const uint4*>(bp[i] + size_t(kb) * kQBlock);
-    }
-    if (tid < FBM) rs = sA_t[size_t(kb) * rows_capacity + srow];
-  };
-  auto lstore = [&](int buf) {
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(ap[i] + size_t(kb) * kQBlock),
+                                       (lptr_t)(As + st * FBM * 8 + (i * 4 + wave) * 64), 16, 0, 0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      As[buf * FBM * 8 + swz(lrow + 32 * i, lpiece)] = ra[i];
-      Bs[buf * FBN * 8 + swz(lrow + 32 * i, lpiece)] = rb[i];
-    }
-    if (tid < FBM) Ss[buf * FBM + tid] = rs;
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(bp[i] + size_t(kb) * kQBlock),
+                                       (lptr_t)(Bs + st * FBN * 8 + (i * 4 + wave) * 64), 16, 0, 0);
   };
 
   f32x16 acc[2][2];
@@ -176,15 +180,18 @@ __global__ __launch_bounds__(256) void fp8act_gemm_kernel(
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
   // B rows of this wavefront's two 32-column blocks
-  const int brow0 = DUAL ? wn * 32 : wn * 64;          // DUAL: gate block; else first block
+  const int brow0 = DUAL ? wn * 32 : wn * 64;             // DUAL: gate block; else first block
   const int brow1 = DUAL ? 64 + wn * 32 : wn * 64 + 32;   // DUAL: the matching up block
 
-  gload(0);
-  lstore(0);
-  __syncthreads();
+  issue(0);
   for (int kb = 0; kb < nkb; ++kb) {
     const int buf = kb & 1;
-    if (kb + 1 < nkb) gload(kb + 1);
+    // step kb has landed (nothing younger is in flight); park its row scales
+    __builtin_amdgcn_s_waitcnt(0x0f70);                   // vmcnt(0)
+    if (tid < FBM) Ss[buf * FBM + tid] = rs;
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // every wavefront is done with step kb-1: refill its stage
+    if (kb + 1 < nkb) issue(kb + 1);
     const uint4* Ab = As + buf * FBM * 8;
     const uint4* Bb = Bs + buf * FBN * 8;
     f32x16 part[2][2];
@@ -236,8 +243,6 @@ __global__ __launch_bounds__(256) void fp8act_gemm_kernel(
         acc[i][1][q] = fmaf(part[i][1][q], sa[q] * sb1, acc[i][1][q]);
       }
     }
-    if (kb + 1 < nkb) lstore(buf ^ 1);
-    __syncthreads();
   }
 
   // D layout: lane l, register q -> row (q/4)*8 + (l/32)*4 + q%4, col l%32
@@ -256,6 +261,18 @@ __global__ __launch_bounds__(256) void fp8act_gemm_kernel(
         C[size_t(row) * N + n0 + wn * 64 + 32 + l31] = f32_to_bf16_bits_rne(acc[i][1][q]);
       }
     }
+}
+
+template <bool DUAL>
+__global__ __launch_bounds__(256, 2) void fp8act_gemm_kernel(
+    const uint8_t* __restrict__ A, const float* __restrict__ sA_t, int rows_capacity,
+    const uint8_t* __restrict__ B0, const uint8_t* __restrict__ B1, const float* __restrict__ S0,
+    const float* __restrict__ S1, uint16_t* __restrict__ C, int N, int K,
+    const int32_t* __restrict__ tiles) {
+  extern __shared__ uint4 fsmem[];
+  // handed on as a generic pointer: with the LDS array named in the loop the
+  // compiler drains every DMA in flight before each LDS read
+  fp8act_gemm_body<DUAL>(A, sA_t, rows_capacity, B0, B1, S0, S1, C, N, K, tiles, fsmem);
 }
 
 }  // namespace
