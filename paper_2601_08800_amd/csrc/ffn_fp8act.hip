@@ -1,7 +1,7 @@
 // Expert FFN with 8-bit activations: both GEMM operands are e4m3, the matrix
 // cores run `v_mfma_f32_32x32x64_f8f6f4` (twice the rate of the bf16 MFMA).
 //
-//   quant   one wavefront per row: per block of 128 columns amax -> scale =
+//   quant   one wavefront per row, 16 lanes per block of 128 columns: amax -> scale =
 //           amax / 448 (1 for an all-zero block), code = e4m3(x / scale) after a
 //           clamp to +-448; codes [rows, K], scales [K/128][rows] (block-major, so
 //           that a tile's scales of one K block are contiguous)
@@ -44,7 +44,32 @@ __device__ __forceinline__ int swz(int row, int piece) {
 
 // ------------------------------------------------------------------ quant
 // x bf16 [rows, K] -> codes [rows, K], scales_t [K/128][rows_capacity].  One
-// wavefront per row; a lane owns two neighbouring columns of every block.
+// wavefront per row walks it in chunks of 512 columns: a lane owns 8
+// neighbouring columns (one 16-byte load), 16 lanes share a block of 128.  Two
+// chunks are in flight per trip.
+__device__ __forceinline__ void quant_piece(const uint4 v, uint2& out, float& scale) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  float f[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = __uint_as_float(w[i] << 16);
+    f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+  float amax = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+#pragma unroll
+  for (int s = 1; s < 16; s <<= 1) amax = fmaxf(amax, __shfl_xor(amax, s));
+  scale = amax > 0.f ? amax / 448.0f : 1.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) f[i] = fminf(fmaxf(f[i] / scale, -448.0f), 448.0f);
+  int lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], 0, false);      // round to nearest even
+  lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+  int hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], 0, false);
+  hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+  out = make_uint2((uint32_t)lo, (uint32_t)hi);
+}
+
 __global__ __launch_bounds__(256) void fp8act_quant_kernel(const uint16_t* __restrict__ x,
                                                           const int32_t* __restrict__ offsets,
                                                           int n_experts, int K, int rows_capacity,
@@ -55,21 +80,27 @@ __global__ __launch_bounds__(256) void fp8act_quant_kernel(const uint16_t* __res
   int rows = offsets[n_experts];
   rows = rows < rows_capacity ? rows : rows_capacity;
   if (row >= rows) return;
-  const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + size_t(row) * K);
-  uint16_t* cr = reinterpret_cast<uint16_t*>(codes + size_t(row) * K);
-  for (int b = 0; b < K / kQBlock; ++b) {
-    const uint32_t two = xr[b * 64 + lane];
-    const float v0 = __uint_as_float(two << 16), v1 = __uint_as_float(two & 0xffff0000u);
-    float amax = fmaxf(fabsf(v0), fabsf(v1));
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) amax = fmaxf(amax, __shfl_xor(amax, s));
-    const float scale = amax > 0.f ? amax / 448.0f : 1.0f;
-    float q0 = v0 / scale, q1 = v1 / scale;
-    q0 = fminf(fmaxf(q0, -448.0f), 448.0f);
-    q1 = fminf(fmaxf(q1, -448.0f), 448.0f);
-    const int packed = __builtin_amdgcn_cvt_pk_fp8_f32(q0, q1, 0, false);   // RNE, low half
-    cr[b * 64 + lane] = (uint16_t)(packed & 0xffff);
-    if (lane == 0) scales_t[size_t(b) * rows_capacity + row] = scale;
+  const uint4* xr = reinterpret_cast<const uint4*>(x + size_t(row) * K);     // 8 columns per piece
+  uint2* cr = reinterpret_cast<uint2*>(codes + size_t(row) * K);
+  const int pieces = K / 8;                       // a multiple of 16
+  const int g = lane >> 4, sub = lane & 15;
+  for (int p0 = 0; p0 < pieces; p0 += 128) {      // the loop bounds are the same in every lane
+    const int pa = p0 + lane, pb = p0 + 64 + lane;
+    const bool ina = pa < pieces, inb = pb < pieces;
+    const uint4 zero = make_uint4(0, 0, 0, 0);
+    const uint4 va = ina ? xr[pa] : zero, vb = inb ? xr[pb] : zero;
+    uint2 ca, cb;
+    float sa, sb;
+    quant_piece(va, ca, sa);
+    quant_piece(vb, cb, sb);
+    if (ina) {
+      cr[pa] = ca;
+      if (sub == 0) scales_t[size_t(p0 / 16 + g) * rows_capacity + row] = sa;
+    }
+    if (inb) {
+      cr[pb] = cb;
+      if (sub == 0) scales_t[size_t(p0 / 16 + 4 + g) * rows_capacity + row] = sb;
+    }
   }
 }
 
