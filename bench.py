@@ -2,7 +2,7 @@
 """Benchmark of one GPU's MoE-layer share: route -> dispatch -> expert FFN ->
 combine on seeded synthetic layers, one JSON line on stdout.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2p|c2d|c3|c3d|c4|c5|c1]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2p|c2d|c3|c3d|c4|c4q|c5|c1]
 
 A step is one pass of the whole path over one batch, inputs resident in HBM.
 `value` is tokens/s of the share; `roofline` prices the dominant kernel against
@@ -30,6 +30,7 @@ DESCR = {
     "c3": "Qwen3-235B-A22B-shaped EP=8 share: 8192 tokens, hidden 4096, 16 of 128 experts, I 1536, bf16",
     "c3d": "Qwen3-235B-A22B-shaped EP=8 share, decode 256 tokens: hidden 4096, 16 of 128 experts, I 1536, bf16",
     "c4": "DeepSeek-R1-shaped TP=2 x EP share: 16384 tokens, hidden 7168, 32 of 256 experts + shared, I 1024, bf16",
+    "c4q": "the c4 share with e4m3 block-128 weights and expert-FFN activations quantised 1x128 to e4m3 (fp8 MFMA)",
     "c5": "DeepSeek-R1-shaped decode stress: 256 tokens, fp8-e4m3 block-128 weights, forced Zipf routing",
 }
 
@@ -91,7 +92,8 @@ def main():
     forced_np = gen.make_forced_routing(w) if w.zipf_s is not None else None
     print("inputs generated in %.1f s" % (time.time() - t0), file=sys.stderr, flush=True)
 
-    L = moe.MoELayerShare(config_from_workload(w), w.T, gate, experts, shared)
+    L = moe.MoELayerShare(config_from_workload(w), w.T, gate, experts, shared,
+                          fp8_activations=w.fp8_activations)
     x = to_device(x_np)
     forced = None if forced_np is None else (to_device(forced_np[0]), to_device(forced_np[1]))
 
@@ -165,7 +167,7 @@ def main():
     # measured inside the timed region; with the shared expert on a second stream
     # the kernels of the two streams share the CUs, so the one-stream pass is used
     dur = (prof[dom][0] if overlap else prof_timed[dom][0]) * 1e-3 / args.steps
-    peak_tf = PEAK_MFMA_TFLOPS[w.weight_dtype]
+    peak_tf = 5000.0 if w.fp8_activations else PEAK_MFMA_TFLOPS[w.weight_dtype]   # fp8 x fp8 MFMA
     t_mfma = fl / (peak_tf * 1e12)
     t_hbm = by / (PEAK_HBM_GBS * 1e9)
     if t_mfma >= t_hbm:
@@ -192,7 +194,7 @@ def main():
         "metric": "moe_layer_share_tokens_per_s", "value": round(value, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": {"f32": "f32", "bf16": "bf16", "fp8": "bf16"}[w.weight_dtype],
+        "vs_baseline": None, "dtype": "fp8" if w.fp8_activations else {"f32": "f32", "bf16": "bf16", "fp8": "bf16"}[w.weight_dtype],
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (w.name, DESCR[w.name]), "tokens": w.T, "hidden": w.H,
                    "experts": w.E, "top_k": w.k, "local_experts": w.E_loc,
@@ -301,7 +303,8 @@ def cpu_baseline(w, x_np, gate, experts, shared, forced_np, budget_s):
                                        gate["logit_bias"], gate["select_bias"])
         else:
             ids, wts = forced_np[0][:n], forced_np[1][:n]
-        oracle.layer_share(xf[:n], ids, wts, w.expert_lo, w.e_hi, ex, sh)
+        oracle.layer_share(xf[:n], ids, wts, w.expert_lo, w.e_hi, ex, sh,
+                           fp8_activations=w.fp8_activations)
         return time.perf_counter() - t0
 
     n = min(w.T, 8)

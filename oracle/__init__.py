@@ -233,19 +233,21 @@ def combine_stage(ys_block, inv, w, out_block=None):
     return out
 
 
-def layer_share(x, ids, w, e_lo, e_hi, experts, shared=None):
+def layer_share(x, ids, w, e_lo, e_hi, experts, shared=None, fp8_activations=False):
     """dispatch -> expert MLP -> (shared expert) -> combine for given routing.
     `experts` / `shared` are dicts with w_gate,w_up,w_down,s_gate,s_up,s_down.
+    `fp8_activations`: both MLPs quantise their activations (expert_ffn_fp8act).
     Returns (out float32 [T,H], parts dict)."""
+    ffn = expert_ffn_fp8act if fp8_activations else expert_ffn
     counts, offsets, perm, inv, xs = dispatch(ids, x, e_lo, e_hi)
-    ys = expert_ffn(offsets, xs, experts["w_gate"], experts["w_up"], experts["w_down"],
-                    experts.get("s_gate"), experts.get("s_up"), experts.get("s_down"))
+    ys = ffn(offsets, xs, experts["w_gate"], experts["w_up"], experts["w_down"],
+             experts.get("s_gate"), experts.get("s_up"), experts.get("s_down"))
     ysh = None
     if shared is not None:
         T = ids.shape[0]
-        ysh = expert_ffn(np.array([0, T], np.int32), x, shared["w_gate"], shared["w_up"],
-                         shared["w_down"], shared.get("s_gate"), shared.get("s_up"),
-                         shared.get("s_down"))
+        ysh = ffn(np.array([0, T], np.int32), x, shared["w_gate"], shared["w_up"],
+                  shared["w_down"], shared.get("s_gate"), shared.get("s_up"),
+                  shared.get("s_down"))
     out = combine(ys, inv, w, ysh)
     return out, {"counts": counts, "offsets": offsets, "perm": perm, "inv": inv, "xs": xs,
                  "ys": ys, "shared_ys": ysh}

@@ -39,8 +39,11 @@ class MoELayerShare:
     GPU's share; `forward()` enqueues route, dispatch, expert FFN (+ shared
     expert) and combine."""
 
-    def __init__(self, cfg: B.MoEConfig, T: int, gate, experts, shared=None, device="cuda"):
+    def __init__(self, cfg: B.MoEConfig, T: int, gate, experts, shared=None, device="cuda",
+                 fp8_activations: bool = False):
         self.cfg, self.T, self.dev = cfg, T, device
+        # both FFN calls go through moe_expert_ffn_fp8act (e4m3 weights required)
+        self.fp8_activations = fp8_activations
         k, H, El = cfg.top_k, cfg.hidden, cfg.n_local
         adt = torch.float32 if cfg.act_dtype == B.MOE_F32 else torch.bfloat16
         self.gate = {n: to_device(v, device) for n, v in gate.items()}
@@ -53,7 +56,13 @@ class MoELayerShare:
         self.perm, self.inv = e(A), e(A)
         self.xs, self.ys = e(A, H, dt=adt), e(A, H, dt=adt)
         self.out = e(T, H, dt=torch.float32)
-        self.ws = e(max(B.moe_workspace_bytes(cfg, T), 256), dt=torch.uint8)
+        ws_bytes = B.moe_workspace_bytes(cfg, T)
+        if fp8_activations:
+            need = max(B.moe_fp8act_workspace_bytes(cfg, El, A), B.moe_fp8act_workspace_bytes(cfg, 1, T))
+            if need == 0:
+                raise ValueError("fp8 activations need bf16 activations, e4m3 weights and sizes that are multiples of 128")
+            ws_bytes = max(ws_bytes, need)
+        self.ws = e(max(ws_bytes, 256), dt=torch.uint8)
         self.shared_ys = None
         # The shared expert depends on x only, not on the routing: by default it is
         # enqueued on a second stream (default priority) with a workspace of its own,
@@ -79,15 +88,17 @@ class MoELayerShare:
 
     def expert_ffn(self, stream=None):
         w = self.experts
-        B.moe_expert_ffn(self.cfg, self.cfg.n_local, self.xs, self.offsets, self.T * self.cfg.top_k,
-                         w["w_gate"], w["w_up"], w["w_down"], w.get("s_gate"), w.get("s_up"),
-                         w.get("s_down"), self.ys, self.ws, stream)
+        fn = B.moe_expert_ffn_fp8act if self.fp8_activations else B.moe_expert_ffn
+        fn(self.cfg, self.cfg.n_local, self.xs, self.offsets, self.T * self.cfg.top_k,
+           w["w_gate"], w["w_up"], w["w_down"], w.get("s_gate"), w.get("s_up"),
+           w.get("s_down"), self.ys, self.ws, stream)
 
     def shared_ffn(self, x, stream=None, ws=None):
         w = self.shared
-        B.moe_expert_ffn(self.cfg, 1, x, self.shared_offsets, self.T, w["w_gate"], w["w_up"],
-                         w["w_down"], w.get("s_gate"), w.get("s_up"), w.get("s_down"),
-                         self.shared_ys, self.ws if ws is None else ws, stream)
+        fn = B.moe_expert_ffn_fp8act if self.fp8_activations else B.moe_expert_ffn
+        fn(self.cfg, 1, x, self.shared_offsets, self.T, w["w_gate"], w["w_up"],
+           w["w_down"], w.get("s_gate"), w.get("s_up"), w.get("s_down"),
+           self.shared_ys, self.ws if ws is None else ws, stream)
 
     def combine(self, stream=None, ys=None):
         B.moe_combine(self.cfg, self.T, self.ys if ys is None else ys, self.inv, self.topk_w,

@@ -31,7 +31,8 @@ def make_layer(w, d):
     from paper_2601_08800_amd import MoELayerShare
     from paper_2601_08800_amd.layer import config_from_workload
     cfg = config_from_workload(w)
-    return MoELayerShare(cfg, w.T, d["gate"], d["experts"], d["shared"])
+    return MoELayerShare(cfg, w.T, d["gate"], d["experts"], d["shared"],
+                         fp8_activations=w.fp8_activations)
 
 
 def dev(a):
@@ -86,5 +87,5 @@ def oracle_out_for_tokens(w, d, tokens, ids, wts):
     """Oracle output rows for a subset of tokens (rows are independent)."""
     x = d["x"][tokens]
     out, _ = oracle.layer_share(x, ids[tokens], wts[tokens], w.expert_lo, w.e_hi, d["experts"],
-                                d["shared"])
+                                d["shared"], fp8_activations=w.fp8_activations)
     return out

@@ -59,6 +59,7 @@ class Workload:
     w_std: float = 0.02
     logit_bias_std: float = 0.0
     select_bias_std: float = 0.0
+    fp8_activations: bool = False    # expert FFN quantises its activations 1x128 to e4m3 on the fly
     zipf_s: Optional[float] = None   # forced Zipf routing exponent, or None
     zipf_perm_stream: int = 0        # which seeded rank->expert permutation is used
 
@@ -96,6 +97,12 @@ CONFIGS: Dict[str, Workload] = {
                    score_fn="sigmoid", routed_scale=2.5, n_groups=8, topk_groups=4,
                    group_score_n=2, expert_lo=0, expert_hi=32, tp=2, tp_rank=0,
                    shared_expert=True, select_bias_std=0.05),
+    # the C4 share with e4m3 weights and 8-bit activations in the expert FFN
+    "c4q": Workload("c4q", 1004, T=16384, H=7168, E=256, k=8, I=2048,
+                    score_fn="sigmoid", routed_scale=2.5, n_groups=8, topk_groups=4,
+                    group_score_n=2, expert_lo=0, expert_hi=32, tp=2, tp_rank=0,
+                    shared_expert=True, select_bias_std=0.05, weight_dtype="fp8",
+                    fp8_activations=True),
     "c5": Workload("c5", 1005, T=256, H=7168, E=256, k=8, I=2048,
                    score_fn="sigmoid", routed_scale=2.5, n_groups=8, topk_groups=4,
                    group_score_n=2, expert_lo=0, expert_hi=32, tp=2, tp_rank=0,
