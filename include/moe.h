@@ -248,6 +248,31 @@ moe_status moe_profile_read(double* total_ms, int32_t* launches);
  * bytes (0 for an unsupported configuration). */
 size_t moe_fp8act_workspace_bytes(const moe_config* cfg, int32_t n_experts_here,
                                   int32_t rows_capacity);
+
+/* The same path with the quantisation taken out of the FFN call, so that a token
+ * is quantised once and its 1-byte codes are what dispatch copies:
+ *   moe_quant_act      x bf16 [rows, hidden] -> codes uint8 [rows, hidden] and
+ *                      scales fp32 [hidden/128][rows] (block-major), by the rule above
+ *   moe_dispatch_fp8q  moe_dispatch on quantised rows: xq [T, hidden] codes with
+ *                      xq_scales [hidden/128][T] -> xs_q [T*k, hidden] codes with
+ *                      xs_scales [hidden/128][T*k] (first A_loc positions valid);
+ *                      counts / offsets / perm / inv exactly as moe_dispatch
+ *   moe_expert_ffn_fp8q  moe_expert_ffn_fp8act on rows that are already quantised:
+ *                      xs_q [rows_capacity, hidden], xs_scales [hidden/128][rows_capacity]
+ * Quantising a row before or after it is copied gives the same codes, so the
+ * results equal those of moe_dispatch + moe_expert_ffn_fp8act bit for bit. */
+moe_status moe_quant_act(const moe_config* cfg, int32_t rows, const void* x, void* codes,
+                         float* scales, void* stream);
+moe_status moe_dispatch_fp8q(const moe_config* cfg, int32_t T, const void* xq,
+                             const float* xq_scales, const int32_t* topk_ids, int32_t* counts,
+                             int32_t* offsets, int32_t* perm, int32_t* inv, void* xs_q,
+                             float* xs_scales, void* ws, size_t ws_bytes, void* stream);
+moe_status moe_expert_ffn_fp8q(const moe_config* cfg, int32_t n_experts_here, const void* xs_q,
+                               const float* xs_scales, const int32_t* offsets,
+                               int32_t rows_capacity, const void* w_gate, const void* w_up,
+                               const void* w_down, const float* s_gate, const float* s_up,
+                               const float* s_down, void* ys, void* ws, size_t ws_bytes,
+                               void* stream);
 moe_status moe_expert_ffn_fp8act(const moe_config* cfg, int32_t n_experts_here, const void* xs,
                                  const int32_t* offsets, int32_t rows_capacity, const void* w_gate,
                                  const void* w_up, const void* w_down, const float* s_gate,

@@ -15,7 +15,8 @@ _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatch",
            "moe_dispatch_shard", "moe_expert_ffn", "moe_combine", "moe_combine_stage",
-           "moe_fp8act_workspace_bytes", "moe_expert_ffn_fp8act",
+           "moe_fp8act_workspace_bytes", "moe_expert_ffn_fp8act", "moe_quant_act",
+           "moe_dispatch_fp8q", "moe_expert_ffn_fp8q",
            "moe_profile_enable", "moe_profile_read",
            "moe_profile_filter",
            "moe_kernel_name")
@@ -74,6 +75,12 @@ def load_library():
         lib.moe_expert_ffn.argtypes = [cfgp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_expert_ffn_fp8act.restype = ctypes.c_int
         lib.moe_expert_ffn_fp8act.argtypes = [cfgp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_quant_act.restype = ctypes.c_int
+        lib.moe_quant_act.argtypes = [cfgp, i32, vp, vp, vp, vp]
+        lib.moe_dispatch_fp8q.restype = ctypes.c_int
+        lib.moe_dispatch_fp8q.argtypes = [cfgp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_expert_ffn_fp8q.restype = ctypes.c_int
+        lib.moe_expert_ffn_fp8q.argtypes = [cfgp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_fp8act_workspace_bytes.restype = sz
         lib.moe_fp8act_workspace_bytes.argtypes = [cfgp, i32, i32]
         lib.moe_combine.restype = ctypes.c_int
@@ -174,6 +181,30 @@ def moe_expert_ffn_fp8act(cfg, n_experts_here, xs, offsets, rows_capacity, w_gat
         _ptr(w_up), _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(ys), _ptr(ws),
         _ws_bytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
     _check(st, "moe_expert_ffn_fp8act")
+
+
+def moe_quant_act(cfg, rows, x, codes, scales, stream=None):
+    st = load_library().moe_quant_act(ctypes.byref(cfg), rows, _ptr(x), _ptr(codes), _ptr(scales),
+                                      _stream(stream))
+    _check(st, "moe_quant_act")
+
+
+def moe_dispatch_fp8q(cfg, T, xq, xq_scales, topk_ids, counts, offsets, perm, inv, xs_q, xs_scales,
+                      ws, stream=None, ws_bytes=None):
+    st = load_library().moe_dispatch_fp8q(
+        ctypes.byref(cfg), T, _ptr(xq), _ptr(xq_scales), _ptr(topk_ids), _ptr(counts), _ptr(offsets),
+        _ptr(perm), _ptr(inv), _ptr(xs_q), _ptr(xs_scales), _ptr(ws),
+        _ws_bytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    _check(st, "moe_dispatch_fp8q")
+
+
+def moe_expert_ffn_fp8q(cfg, n_experts_here, xs_q, xs_scales, offsets, rows_capacity, w_gate, w_up,
+                        w_down, s_gate, s_up, s_down, ys, ws, stream=None, ws_bytes=None):
+    st = load_library().moe_expert_ffn_fp8q(
+        ctypes.byref(cfg), n_experts_here, _ptr(xs_q), _ptr(xs_scales), _ptr(offsets), rows_capacity,
+        _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(s_gate), _ptr(s_up), _ptr(s_down), _ptr(ys),
+        _ptr(ws), _ws_bytes(ws) if ws_bytes is None else ws_bytes, _stream(stream))
+    _check(st, "moe_expert_ffn_fp8q")
 
 
 def moe_combine(cfg, T, ys, inv, topk_w, shared_ys, out, stream=None):

@@ -311,18 +311,41 @@ __global__ __launch_bounds__(256) void dispatch_small_kernel(
   }
 }
 
+// Per-row block scales follow their rows: out[kb][pos] = in[kb][token of pos] for
+// the valid positions (both arrays are block-major: one row of the array per
+// 128-column block).
+__global__ __launch_bounds__(256) void dispatch_scales_kernel(
+    const float* __restrict__ in, int in_pitch, const int32_t* __restrict__ perm,
+    const int32_t* __restrict__ offsets, int E_loc, int k, int n_blocks, float* __restrict__ out,
+    int out_pitch) {
+  const int pos = blockIdx.x * 256 + threadIdx.x;
+  if (pos >= offsets[E_loc] || pos >= out_pitch) return;
+  const int t = perm[pos] / k;
+  for (int kb = 0; kb < n_blocks; ++kb) out[size_t(kb) * out_pitch + pos] = in[size_t(kb) * in_pitch + t];
+}
+
 }  // namespace
+
+hipError_t launch_dispatch_scales(const float* in, int in_pitch, const int32_t* perm,
+                                  const int32_t* offsets, int E_loc, int k, int n_blocks, float* out,
+                                  int out_pitch, hipStream_t s) {
+  MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_scales_kernel, dim3((out_pitch + 255) / 256), dim3(256), 0, s,
+             in, in_pitch, perm, offsets, E_loc, k, n_blocks, out, out_pitch);
+  return hipGetLastError();
+}
 
 hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int32_t* ids,
                            int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
                            void* xs, int tp_rank, int tp_size, const DispatchWs& ws,
-                           hipStream_t s) {
+                           hipStream_t s, int elem_bytes) {
   const int k = c.top_k;
   const int A = T * k;
   const int E_loc = c.expert_hi - c.expert_lo;
   const int n_sub = (A + kSub - 1) / kSub;
-  // column window of TP rank tp_rank of tp_size (the whole row for 0 of 1)
-  const int src16 = c.hidden * (c.act_dtype == MOE_F32 ? 4 : 2) / 16;
+  // column window of TP rank tp_rank of tp_size (the whole row for 0 of 1);
+  // elem_bytes overrides the element size of the rows (1: quantised codes)
+  if (elem_bytes == 0) elem_bytes = c.act_dtype == MOE_F32 ? 4 : 2;
+  const int src16 = c.hidden * elem_bytes / 16;
   const int row16 = src16 / tp_size;
   if (A <= kSmallA && small_lds_bytes(E_loc, n_sub) <= kSmallLds) {
     MOE_LAUNCH(MOE_K_DISPATCH_GATHER, dispatch_small_kernel<8>, dim3((T + 3) / 4), dim3(256),

@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void fp8act_quant_kernel(const uint16_t* __res
                                                           float* __restrict__ scales_t) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  int rows = offsets[n_experts];
+  int rows = offsets ? offsets[n_experts] : rows_capacity;     // no offsets: every row
   rows = rows < rows_capacity ? rows : rows_capacity;
   if (row >= rows) return;
   const uint4* xr = reinterpret_cast<const uint4*>(x + size_t(row) * K);     // 8 columns per piece
@@ -352,16 +352,18 @@ size_t moe_fp8act_workspace_bytes(const moe_config* cfg, int32_t n_experts_here,
   return carve_fp8act(nullptr, rows_capacity, n_experts_here, cfg->hidden, cfg->inter_local).bytes;
 }
 
-moe_status moe_expert_ffn_fp8act(const moe_config* cfg, int32_t n_experts_here, const void* xs,
-                                 const int32_t* offsets, int32_t rows_capacity, const void* w_gate,
-                                 const void* w_up, const void* w_down, const float* s_gate,
-                                 const float* s_up, const float* s_down, void* ys, void* ws,
-                                 size_t ws_bytes, void* stream) {
+// shared by the two FFN entry points: xs_q / xs_scales given -> no input quantisation
+static moe_status fp8act_run(const moe_config* cfg, int32_t n_experts_here, const void* xs,
+                             const void* xs_q, const float* xs_scales, const int32_t* offsets,
+                             int32_t rows_capacity, const void* w_gate, const void* w_up,
+                             const void* w_down, const float* s_gate, const float* s_up,
+                             const float* s_down, void* ys, void* ws, size_t ws_bytes, void* stream) {
   if (!cfg) return MOE_ERR_INVALID_ARG;
   if (!fp8act_ok(cfg)) return MOE_ERR_UNSUPPORTED;
   if (n_experts_here < 1 || n_experts_here > 512 || rows_capacity < 0) return MOE_ERR_INVALID_ARG;
   if (rows_capacity == 0) return MOE_OK;
-  const void* ptrs[] = {xs, offsets, w_gate, w_up, w_down, s_gate, s_up, s_down, ys, ws};
+  const void* ptrs[] = {xs ? xs : xs_q, xs ? xs : static_cast<const void*>(xs_scales), offsets, w_gate,
+                        w_up, w_down, s_gate, s_up, s_down, ys, ws};
   for (const void* p : ptrs)
     if (!p || (reinterpret_cast<uintptr_t>(p) & 15)) return MOE_ERR_INVALID_ARG;
   const int H = cfg->hidden, I = cfg->inter_local;
@@ -377,9 +379,15 @@ moe_status moe_expert_ffn_fp8act(const moe_config* cfg, int32_t n_experts_here, 
   const dim3 qgrid((rows_capacity + 3) / 4);
   MOE_LAUNCH(MOE_K_FFN_TILES, fp8act_tiles_kernel, dim3(1), dim3(512), 0, s, offsets, n_experts_here,
              rows_capacity, f.tiles, f.max_tiles);
-  MOE_LAUNCH(MOE_K_FFN_TILES, fp8act_quant_kernel, qgrid, dim3(256), 0, s,
-             static_cast<const uint16_t*>(xs), offsets, n_experts_here, H, rows_capacity, f.xq, f.xs_t);
-  MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(size_t(f.max_tiles) * (I / 64)), dim3(256), lds, s, f.xq, f.xs_t,
+  const uint8_t* aq = static_cast<const uint8_t*>(xs_q);
+  const float* as = xs_scales;
+  if (xs) {
+    MOE_LAUNCH(MOE_K_FFN_TILES, fp8act_quant_kernel, qgrid, dim3(256), 0, s,
+               static_cast<const uint16_t*>(xs), offsets, n_experts_here, H, rows_capacity, f.xq, f.xs_t);
+    aq = f.xq;
+    as = f.xs_t;
+  }
+  MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(size_t(f.max_tiles) * (I / 64)), dim3(256), lds, s, aq, as,
              rows_capacity, static_cast<const uint8_t*>(w_gate), static_cast<const uint8_t*>(w_up),
              s_gate, s_up, f.hmid, I, H, f.tiles);
   MOE_LAUNCH(MOE_K_FFN_TILES, fp8act_quant_kernel, qgrid, dim3(256), 0, s, f.hmid, offsets,
@@ -388,6 +396,43 @@ moe_status moe_expert_ffn_fp8act(const moe_config* cfg, int32_t n_experts_here, 
              rows_capacity, static_cast<const uint8_t*>(w_down), static_cast<const uint8_t*>(nullptr),
              s_down, static_cast<const float*>(nullptr), static_cast<uint16_t*>(ys), H, I, f.tiles);
   return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
+}
+
+moe_status moe_quant_act(const moe_config* cfg, int32_t rows, const void* x, void* codes,
+                         float* scales, void* stream) {
+  if (!cfg) return MOE_ERR_INVALID_ARG;
+  if (cfg->act_dtype != MOE_BF16 || cfg->hidden <= 0 || cfg->hidden % 128) return MOE_ERR_UNSUPPORTED;
+  if (rows < 0) return MOE_ERR_INVALID_ARG;
+  if (rows == 0) return MOE_OK;
+  const void* ptrs[] = {x, codes, scales};
+  for (const void* p : ptrs)
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 15)) return MOE_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  MOE_LAUNCH(MOE_K_FFN_TILES, fp8act_quant_kernel, dim3((rows + 3) / 4), dim3(256), 0, s,
+             static_cast<const uint16_t*>(x), static_cast<const int32_t*>(nullptr), 0, cfg->hidden, rows,
+             static_cast<uint8_t*>(codes), scales);
+  return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
+}
+
+moe_status moe_expert_ffn_fp8act(const moe_config* cfg, int32_t n_experts_here, const void* xs,
+                                 const int32_t* offsets, int32_t rows_capacity, const void* w_gate,
+                                 const void* w_up, const void* w_down, const float* s_gate,
+                                 const float* s_up, const float* s_down, void* ys, void* ws,
+                                 size_t ws_bytes, void* stream) {
+  if (!xs) return MOE_ERR_INVALID_ARG;
+  return fp8act_run(cfg, n_experts_here, xs, nullptr, nullptr, offsets, rows_capacity, w_gate, w_up,
+                    w_down, s_gate, s_up, s_down, ys, ws, ws_bytes, stream);
+}
+
+moe_status moe_expert_ffn_fp8q(const moe_config* cfg, int32_t n_experts_here, const void* xs_q,
+                               const float* xs_scales, const int32_t* offsets,
+                               int32_t rows_capacity, const void* w_gate, const void* w_up,
+                               const void* w_down, const float* s_gate, const float* s_up,
+                               const float* s_down, void* ys, void* ws, size_t ws_bytes,
+                               void* stream) {
+  if (!xs_q || !xs_scales) return MOE_ERR_INVALID_ARG;
+  return fp8act_run(cfg, n_experts_here, nullptr, xs_q, xs_scales, offsets, rows_capacity, w_gate,
+                    w_up, w_down, s_gate, s_up, s_down, ys, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -135,7 +135,7 @@ bool shard_ok(const moe_config* cfg, int32_t tp_rank, int32_t tp_size) {
 moe_status dispatch_impl(const moe_config* cfg, int32_t T, const void* x, const int32_t* topk_ids,
                          int32_t tp_rank, int32_t tp_size, int32_t* counts, int32_t* offsets,
                          int32_t* perm, int32_t* inv, void* xs, void* ws, size_t ws_bytes,
-                         void* stream) {
+                         void* stream, int elem_bytes = 0) {
   moe_status st = check_config(cfg);
   if (st != MOE_OK) return st;
   if (T < 0 || !shard_ok(cfg, tp_rank, tp_size)) return MOE_ERR_INVALID_ARG;
@@ -149,7 +149,7 @@ moe_status dispatch_impl(const moe_config* cfg, int32_t T, const void* x, const 
   DispatchWs d = carve_dispatch(ws, T, cfg->top_k, cfg->expert_hi - cfg->expert_lo);
   if (ws_bytes < d.bytes) return MOE_ERR_WORKSPACE;
   hipError_t e = launch_dispatch(*cfg, T, x, topk_ids, counts, offsets, perm, inv, xs, tp_rank,
-                                 tp_size, d, static_cast<hipStream_t>(stream));
+                                 tp_size, d, static_cast<hipStream_t>(stream), elem_bytes);
   return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
 }
 }  // namespace
@@ -168,6 +168,23 @@ moe_status moe_dispatch_shard(const moe_config* cfg, int32_t T, const void* x,
                               void* xs_shard, void* ws, size_t ws_bytes, void* stream) {
   return dispatch_impl(cfg, T, x, topk_ids, tp_rank, tp_size, counts, offsets, perm, inv, xs_shard,
                        ws, ws_bytes, stream);
+}
+
+moe_status moe_dispatch_fp8q(const moe_config* cfg, int32_t T, const void* xq,
+                             const float* xq_scales, const int32_t* topk_ids, int32_t* counts,
+                             int32_t* offsets, int32_t* perm, int32_t* inv, void* xs_q,
+                             float* xs_scales, void* ws, size_t ws_bytes, void* stream) {
+  if (!cfg) return MOE_ERR_INVALID_ARG;
+  if (cfg->hidden % 128) return MOE_ERR_UNSUPPORTED;
+  if (!xq_scales || !xs_scales || !aligned16(xq_scales) || !aligned16(xs_scales))
+    return MOE_ERR_INVALID_ARG;
+  moe_status st = dispatch_impl(cfg, T, xq, topk_ids, 0, 1, counts, offsets, perm, inv, xs_q, ws,
+                                ws_bytes, stream, 1);
+  if (st != MOE_OK || T == 0) return st;
+  hipError_t e = launch_dispatch_scales(xq_scales, T, perm, offsets, cfg->expert_hi - cfg->expert_lo,
+                                        cfg->top_k, cfg->hidden / 128, xs_scales, T * cfg->top_k,
+                                        static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? MOE_OK : MOE_ERR_DEVICE;
 }
 
 moe_status moe_expert_ffn(const moe_config* cfg, int32_t n_experts_here, const void* xs,

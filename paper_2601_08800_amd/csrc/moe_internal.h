@@ -84,7 +84,11 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
 hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int32_t* ids,
                            int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv,
                            void* xs, int tp_rank, int tp_size, const DispatchWs& ws,
-                           hipStream_t s);
+                           hipStream_t s, int elem_bytes = 0);
+
+hipError_t launch_dispatch_scales(const float* in, int in_pitch, const int32_t* perm,
+                                  const int32_t* offsets, int E_loc, int k, int n_blocks, float* out,
+                                  int out_pitch, hipStream_t s);
 
 hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
                              const int32_t* offsets, int rows_capacity, const void* w_gate,

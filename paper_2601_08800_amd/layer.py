@@ -63,6 +63,9 @@ class MoELayerShare:
                 raise ValueError("fp8 activations need bf16 activations, e4m3 weights and sizes that are multiples of 128")
             ws_bytes = max(ws_bytes, need)
         self.ws = e(max(ws_bytes, 256), dt=torch.uint8)
+        if fp8_activations:      # a token is quantised once; dispatch copies the 1-byte codes
+            self.xq, self.xq_scales = e(T, H, dt=torch.uint8), e(H // 128, T, dt=torch.float32)
+            self.xs_q, self.xs_scales = e(A, H, dt=torch.uint8), e(H // 128, A, dt=torch.float32)
         self.shared_ys = None
         # The shared expert depends on x only, not on the routing: by default it is
         # enqueued on a second stream (default priority) with a workspace of its own,
@@ -83,22 +86,35 @@ class MoELayerShare:
                     logits_in, self.topk_ids, self.topk_w, self.ws, stream)
 
     def dispatch(self, x, stream=None):
+        if self.fp8_activations:      # x was quantised by forward()
+            B.moe_dispatch_fp8q(self.cfg, self.T, self.xq, self.xq_scales, self.topk_ids, self.counts,
+                                self.offsets, self.perm, self.inv, self.xs_q, self.xs_scales, self.ws,
+                                stream)
+            return
         B.moe_dispatch(self.cfg, self.T, x, self.topk_ids, self.counts, self.offsets, self.perm,
                        self.inv, self.xs, self.ws, stream)
 
     def expert_ffn(self, stream=None):
         w = self.experts
-        fn = B.moe_expert_ffn_fp8act if self.fp8_activations else B.moe_expert_ffn
-        fn(self.cfg, self.cfg.n_local, self.xs, self.offsets, self.T * self.cfg.top_k,
-           w["w_gate"], w["w_up"], w["w_down"], w.get("s_gate"), w.get("s_up"),
-           w.get("s_down"), self.ys, self.ws, stream)
+        if self.fp8_activations:
+            B.moe_expert_ffn_fp8q(self.cfg, self.cfg.n_local, self.xs_q, self.xs_scales, self.offsets,
+                                  self.T * self.cfg.top_k, w["w_gate"], w["w_up"], w["w_down"],
+                                  w["s_gate"], w["s_up"], w["s_down"], self.ys, self.ws, stream)
+            return
+        B.moe_expert_ffn(self.cfg, self.cfg.n_local, self.xs, self.offsets, self.T * self.cfg.top_k,
+                         w["w_gate"], w["w_up"], w["w_down"], w.get("s_gate"), w.get("s_up"),
+                         w.get("s_down"), self.ys, self.ws, stream)
 
     def shared_ffn(self, x, stream=None, ws=None):
         w = self.shared
-        fn = B.moe_expert_ffn_fp8act if self.fp8_activations else B.moe_expert_ffn
-        fn(self.cfg, 1, x, self.shared_offsets, self.T, w["w_gate"], w["w_up"],
-           w["w_down"], w.get("s_gate"), w.get("s_up"), w.get("s_down"),
-           self.shared_ys, self.ws if ws is None else ws, stream)
+        if self.fp8_activations:      # on the rows forward() quantised
+            B.moe_expert_ffn_fp8q(self.cfg, 1, self.xq, self.xq_scales, self.shared_offsets, self.T,
+                                  w["w_gate"], w["w_up"], w["w_down"], w["s_gate"], w["s_up"],
+                                  w["s_down"], self.shared_ys, self.ws if ws is None else ws, stream)
+            return
+        B.moe_expert_ffn(self.cfg, 1, x, self.shared_offsets, self.T, w["w_gate"], w["w_up"],
+                         w["w_down"], w.get("s_gate"), w.get("s_up"), w.get("s_down"),
+                         self.shared_ys, self.ws if ws is None else ws, stream)
 
     def combine(self, stream=None, ys=None):
         B.moe_combine(self.cfg, self.T, self.ys if ys is None else ys, self.inv, self.topk_w,
@@ -126,6 +142,8 @@ class MoELayerShare:
         """One pass of the whole path.  `forced` = (ids, w) device tensors to
         bypass the gate (forced-routing stress case)."""
         concurrent = self.shared is not None and self.overlap_shared
+        if self.fp8_activations:
+            B.moe_quant_act(self.cfg, self.T, x, self.xq, self.xq_scales, stream)
         if concurrent:
             main = torch.cuda.current_stream() if stream is None else stream
             self.side_stream.wait_stream(main)       # x ready; the previous combine has read shared_ys

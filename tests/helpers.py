@@ -73,8 +73,14 @@ def check_dispatch(L, ids, w, x_np, want_rows=True):
         k = w.k
         rows = np.unique(np.concatenate([np.arange(min(n, 64)), np.arange(max(0, n - 64), n),
                                          np.random.default_rng(1).integers(0, n, 256)]))
-        xs = host(L.xs[torch.from_numpy(rows).to(L.xs.device)])
-        assert np.array_equal(xs, x_np[perm[rows] // k])
+        sel = torch.from_numpy(rows).to(L.xs.device)
+        if w.fp8_activations:      # dispatch copied the tokens' e4m3 codes and block scales
+            codes, scales = oracle.quant_act_1x128(x_np[perm[rows] // k])
+            got = host(L.xs_q[sel])
+            assert (((got == codes) | (((got | codes) & 0x7F) == 0))).all()
+            assert np.array_equal(host(L.xs_scales[:, sel]).T, scales)
+        else:
+            assert np.array_equal(host(L.xs[sel]), x_np[perm[rows] // k])
     return c, o, perm, inv
 
 

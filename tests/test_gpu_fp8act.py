@@ -97,3 +97,58 @@ def test_fp8act_argument_validation():
     assert moe.moe_fp8act_workspace_bytes(bad, 4, 100) == 0
     bf = config_from_workload(w.replace(weight_dtype="bf16"))
     assert moe.moe_fp8act_workspace_bytes(bf, 4, 100) == 0
+
+
+def test_quantise_once_path_equals_the_fused_call():
+    """moe_quant_act + moe_dispatch_fp8q + moe_expert_ffn_fp8q against the oracle's
+    quantiser and dispatch (bit-exact) and against moe_dispatch + moe_expert_ffn_fp8act
+    (the same bits: a row is quantised the same way before or after it is copied)."""
+    w = BASE.replace(name="f8a_once", T=333, H=384, I=256, E=12, k=3, expert_lo=2, expert_hi=9, seed=75)
+    cfg = config_from_workload(w)
+    T, k, H, A, El = w.T, w.k, w.H, w.T * w.k, w.e_hi - w.expert_lo
+    rng = np.random.default_rng(9)
+    x_np = gen.make_x(w)
+    ids = rng.integers(0, w.E, (T, k)).astype(np.int32)
+    ex = gen.make_local_experts(w)
+    dw = [dev(ex[n]) for n in ("w_gate", "w_up", "w_down", "s_gate", "s_up", "s_down")]
+    x = dev(x_np)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    u8 = dict(dtype=torch.uint8, device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(moe.moe_workspace_bytes(cfg, T), moe.moe_fp8act_workspace_bytes(cfg, El, A)), **u8)
+
+    # quantise once
+    xq, xq_s = torch.empty(T, H, **u8), torch.empty(H // 128, T, **f32)
+    moe.moe_quant_act(cfg, T, x, xq, xq_s)
+    torch.cuda.synchronize()
+    codes_ref, scales_ref = oracle.quant_act_1x128(x_np)
+    got_c = host(xq)
+    assert (((got_c == codes_ref) | (((got_c | codes_ref) & 0x7F) == 0))).all()
+    assert np.array_equal(host(xq_s).T, scales_ref)
+
+    # dispatch the codes
+    counts, offsets = torch.empty(El, **i32), torch.empty(El + 1, **i32)
+    perm, inv = torch.empty(A, **i32), torch.empty(A, **i32)
+    xs_q, xs_s = torch.zeros(A, H, **u8), torch.zeros(H // 128, A, **f32)
+    moe.moe_dispatch_fp8q(cfg, T, xq, xq_s, dev(ids), counts, offsets, perm, inv, xs_q, xs_s, ws)
+    torch.cuda.synchronize()
+    c_ref, o_ref, p_ref, i_ref, _ = oracle.dispatch(ids, None, w.expert_lo, w.e_hi, want_xs=False)
+    n = int(o_ref[-1])
+    assert np.array_equal(host(counts), c_ref) and np.array_equal(host(offsets), o_ref)
+    assert np.array_equal(host(perm)[:n], p_ref) and np.array_equal(host(inv), i_ref)
+    assert np.array_equal(host(xs_q)[:n], got_c[p_ref // k])
+    assert np.array_equal(host(xs_s)[:, :n], host(xq_s)[:, p_ref // k])
+
+    # FFN on the dispatched codes == FFN that quantises the dispatched bf16 rows itself
+    ys_a = torch.zeros(A, H, dtype=torch.bfloat16, device="cuda")
+    moe.moe_expert_ffn_fp8q(cfg, El, xs_q, xs_s, offsets, A, *dw, ys_a, ws)
+    xs = torch.zeros(A, H, dtype=torch.bfloat16, device="cuda")
+    c2, o2, p2, i2 = (torch.empty_like(t) for t in (counts, offsets, perm, inv))
+    moe.moe_dispatch(cfg, T, x, dev(ids), c2, o2, p2, i2, xs, ws)
+    ys_b = torch.zeros(A, H, dtype=torch.bfloat16, device="cuda")
+    moe.moe_expert_ffn_fp8act(cfg, El, xs, o2, A, *dw, ys_b, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ys_a[:n].view(torch.int16), ys_b[:n].view(torch.int16))
+    ref = oracle.expert_ffn_fp8act(o_ref, x_np[p_ref // k], ex["w_gate"], ex["w_up"], ex["w_down"],
+                                   ex["s_gate"], ex["s_up"], ex["s_down"])
+    assert rel_err(oracle.decode(host(ys_a))[:n], ref[:n]) <= 6e-2
