@@ -21,6 +21,9 @@ import numpy as np
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "moe_oracle.c")
 _LIB = os.path.join(_DIR, "liboracle.so")
+# A test that plants mistakes in a copy of the source points this at the copy's
+# build; the library is then loaded as it is and never rebuilt from _SRC.
+_LIB_OVERRIDE = os.environ.get("MOE_ORACLE_LIB")
 _lib = None
 
 SCORE_SOFTMAX, SCORE_SIGMOID = 0, 1
@@ -28,6 +31,8 @@ SCORE_SOFTMAX, SCORE_SIGMOID = 0, 1
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if _LIB_OVERRIDE:
+        return _LIB_OVERRIDE
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
@@ -39,8 +44,7 @@ def build(force: bool = False) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        _lib = ctypes.CDLL(build())
         _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
 

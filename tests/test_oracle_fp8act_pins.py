@@ -60,7 +60,8 @@ def _weights(ex, name, sname, e):
 
 
 def test_ffn_equals_a_composition_of_library_routines():
-    w, ex, offsets, xs = _case(31)
+    # 3 x 2 blocks of weight scales, two blocks of hidden-activation scales
+    w, ex, offsets, xs = _case(31, H=384, I=256)
     ys = oracle.expert_ffn_fp8act(offsets, xs, ex["w_gate"], ex["w_up"], ex["w_down"],
                                   ex["s_gate"], ex["s_up"], ex["s_down"])
 

@@ -134,21 +134,20 @@ def test_ffn_tp_additivity():
 
 
 def test_ffn_block_scales():
+    # a 3 x 2 grid of blocks (I = 384, H = 256) with a different power of two in every
+    # block, so that a transposed or shifted block index changes the result
     rng = np.random.default_rng(8)
-    R, H, I = 3, 256, 128
+    R, H, I = 3, 256, 384
     xs = rng.standard_normal((R, H)).astype(np.float32)
     wg = rng.standard_normal((1, I, H)).astype(np.float32)
     wu = rng.standard_normal((1, I, H)).astype(np.float32)
     wd = rng.standard_normal((1, H, I)).astype(np.float32)
-    sg = np.array([[[0.5, 2.0]]], np.float32)           # [1, I/128, H/128]
-    su = np.array([[[4.0, 0.25]]], np.float32)
-    sd = np.array([[[2.0], [8.0]]], np.float32)         # [1, H/128, I/128]
+    sg = np.array([[[0.5, 2.0], [8.0, 0.125], [1.0, 32.0]]], np.float32)       # [1, I/128, H/128]
+    su = np.array([[[4.0, 0.25], [0.5, 16.0], [2.0, 0.0625]]], np.float32)
+    sd = np.array([[[2.0, 0.5, 64.0], [8.0, 0.25, 1.0]]], np.float32)          # [1, H/128, I/128]
     ys = oracle.expert_ffn(np.array([0, R], np.int32), xs, wg, wu, wd, sg, su, sd)
-    wg2, wu2, wd2 = wg.copy(), wu.copy(), wd.copy()
-    wg2[:, :, :128] *= 0.5; wg2[:, :, 128:] *= 2.0
-    wu2[:, :, :128] *= 4.0; wu2[:, :, 128:] *= 0.25
-    wd2[:, :128, :] *= 2.0; wd2[:, 128:, :] *= 8.0      # power-of-two scales: exact
-    ref = _mlp_ref(xs, wg2[0], wu2[0], wd2[0])
+    blow = lambda s: np.kron(s[0], np.ones((128, 128), np.float32))            # power-of-two scales: exact
+    ref = _mlp_ref(xs, wg[0] * blow(sg), wu[0] * blow(su), wd[0] * blow(sd))
     np.testing.assert_allclose(ys, ref, rtol=1e-11, atol=1e-12 * np.abs(ref).max())
 
 
