@@ -88,6 +88,9 @@ CONFIGS: Dict[str, Workload] = {
                    weight_dtype="f32", x_std=0.02),
     "c2p": Workload("c2p", 1002, T=4096, H=2048, E=128, k=8, I=768),
     "c2d": Workload("c2d", 1002, T=64, H=2048, E=128, k=8, I=768),
+    # the largest step the paper's serving limits allow (evaluation set-up: at most
+    # 16 sequences of at most 4096 tokens): send and return buffers above 2 GiB
+    "c2x": Workload("c2x", 1002, T=65536, H=2048, E=128, k=8, I=768),
     "c3": Workload("c3", 1003, T=8192, H=4096, E=128, k=8, I=1536,
                    expert_lo=0, expert_hi=16, logit_bias_std=0.5),
     # the same EP=8 share at a decode batch (256 tokens in flight)
