@@ -20,11 +20,10 @@ void prof_mark(int kernel_id, hipStream_t s, bool begin) {
   if (begin) {
     if (g_used >= g_pool.size()) { g_open = false; return; }
     g_pool[g_used].id = kernel_id;
-    hipEventRecord(g_pool[g_used].a, s);
-    g_open = true;
+    // a record whose begin or end mark fails is dropped, not read later
+    g_open = hipEventRecord(g_pool[g_used].a, s) == hipSuccess;
   } else if (g_open) {
-    hipEventRecord(g_pool[g_used].b, s);
-    ++g_used;
+    if (hipEventRecord(g_pool[g_used].b, s) == hipSuccess) ++g_used;
     g_open = false;
   }
 }
@@ -38,15 +37,23 @@ extern "C" {
 moe_status moe_profile_enable(int32_t max_records) {
   if (max_records < 0) return MOE_ERR_INVALID_ARG;
   g_prof_on = false;
-  for (auto& r : g_pool) { hipEventDestroy(r.a); hipEventDestroy(r.b); }
+  for (auto& r : g_pool) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   g_pool.clear();
   g_used = 0;
   g_open = false;
   if (max_records == 0) return MOE_OK;
-  g_pool.resize(max_records);
-  for (auto& r : g_pool) {
-    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess)
-      return MOE_ERR_DEVICE;
+  g_pool.reserve(max_records);
+  for (int32_t i = 0; i < max_records; ++i) {
+    Rec r;
+    r.id = 0;
+    if (hipEventCreate(&r.a) != hipSuccess) break;
+    if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); break; }
+    g_pool.push_back(r);       // the pool only ever holds pairs that exist
+  }
+  if (g_pool.size() != size_t(max_records)) {
+    for (auto& r : g_pool) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    g_pool.clear();
+    return MOE_ERR_DEVICE;
   }
   g_prof_on = true;
   return MOE_OK;
