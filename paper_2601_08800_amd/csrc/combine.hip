@@ -43,7 +43,12 @@ __global__ __launch_bounds__(256) void combine_bf16_kernel(
     const uint4* __restrict__ shared_ys, float4* __restrict__ out, int T, int k, int row8,
     int accumulate) {
   const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  constexpr int P = 4;                          // pieces per lane in flight
+  // a wavefront owns one segment of 64*P pieces of one token's row: wide rows are
+  // shared out over several wavefronts, each with one round of loads and stores
+  const int nseg = (row8 + 64 * P - 1) / (64 * P);
+  const int gw = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const int t = gw / nseg;
   if (t >= T) return;
   int pos = -1;
   float wt = 0.f;
@@ -52,9 +57,9 @@ __global__ __launch_bounds__(256) void combine_bf16_kernel(
     wt = w[size_t(t) * k + lane];
   }
   const uint64_t have = __ballot(pos >= 0);
-  constexpr int P = 4;                          // pieces per lane in flight
-  // the loop bounds are the same in every lane (the shuffles below need all of them)
-  for (int cb = 0; cb < row8; cb += 64 * P) {
+  // every lane of the wavefront runs the body (the shuffles below need all of them)
+  {
+    const int cb = (gw - t * nseg) * 64 * P;
     const int c0 = cb + lane;
     float acc[P][8];
 #pragma unroll
@@ -159,8 +164,11 @@ __global__ __launch_bounds__(256) void combine_f32_kernel(
 hipError_t launch_combine(const moe_config& c, int T, const void* ys, const int32_t* inv,
                           const float* w, const void* shared_ys, float* out, int width,
                           int accumulate, hipStream_t s) {
-  const dim3 grid((T + 3) / 4), block(256);
+  const dim3 block(256);
+  dim3 grid((T + 3) / 4);
   if (c.act_dtype == MOE_BF16) {
+    const size_t nseg = (size_t(width / 8) + 255) / 256;      // wavefronts per token row
+    grid = dim3(unsigned((size_t(T) * nseg + 3) / 4));
     MOE_LAUNCH(MOE_K_COMBINE, combine_bf16_kernel, grid, block, 0, s, static_cast<const uint4*>(ys), inv,
                        w, static_cast<const uint4*>(shared_ys), reinterpret_cast<float4*>(out), T,
                        c.top_k, width / 8, accumulate);
