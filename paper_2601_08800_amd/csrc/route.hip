@@ -66,35 +66,70 @@ __device__ __forceinline__ double lane_xchg(double v) {
 
 #define MOE_ALL_STEPS(F) F(0) F(1) F(2) F(3) F(4) F(5)
 
+// Value of lane `l` (the same l in every lane) as a scalar broadcast: no LDS crossbar.
+__device__ __forceinline__ int read_lane(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
+__device__ __forceinline__ float read_lane(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+__device__ __forceinline__ double read_lane(double v, int l) {
+  const uint64_t u = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, l);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), l);
+  return __builtin_bit_cast(double, (uint64_t(hi) << 32) | lo);
+}
+
+__device__ __forceinline__ int lane_id() {
+  return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
+// Sum over the wave in a fixed order, the same in every lane: a butterfly inside
+// each row of 16 lanes, then (row0 + row1) + (row2 + row3) from the row results
+// read as scalars.
 template <typename T>
 __device__ __forceinline__ T wave_sum(T v) {
 #define STEP_(S) v += lane_xchg<S>(v);
-  MOE_ALL_STEPS(STEP_)
+  STEP_(0) STEP_(1) STEP_(2) STEP_(3)
 #undef STEP_
-  return v;
+  const T r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
+  return (r0 + r1) + (r2 + r3);
 }
 
+// Largest value over the wave, the same in every lane: the four DPP steps make
+// each row of 16 lanes uniform, the four row results are then read as scalars.
 template <typename T>
 __device__ __forceinline__ T wave_max(T v) {
 #define STEP_(S) { const T o = lane_xchg<S>(v); v = o > v ? o : v; }
+  STEP_(0) STEP_(1) STEP_(2) STEP_(3)
+#undef STEP_
+  const T r0 = read_lane(v, 0), r1 = read_lane(v, 16), r2 = read_lane(v, 32), r3 = read_lane(v, 48);
+  const T a = r1 > r0 ? r1 : r0, b = r3 > r2 ? r3 : r2;
+  return b > a ? b : a;
+}
+
+__device__ __forceinline__ int wave_min(int v) {
+#define STEP_(S) { const int o = lane_xchg<S>(v); v = o < v ? o : v; }
   MOE_ALL_STEPS(STEP_)
 #undef STEP_
   return v;
 }
 
 // Largest value over the wave, ties to the lowest index; idx == INT_MAX marks
-// "no candidate".  Result is the same in every lane.
+// "no candidate".  Result is the same in every lane.  The maximum is a plain
+// wave_max; the lanes that hold it answer a ballot, and the usual single winner's
+// index is read from its lane (a minimum over the tied lanes otherwise).
 template <typename T>
 __device__ __forceinline__ void wave_argmax(T& v, int& idx) {
-#define STEP_(S)                                                                          \
-  {                                                                                       \
-    const T ov = lane_xchg<S>(v);                                                         \
-    const int oi = lane_xchg<S>(idx);                                                     \
-    const bool take = (oi != INT_MAX) && (idx == INT_MAX || ov > v || (ov == v && oi < idx)); \
-    if (take) { v = ov; idx = oi; }                                                       \
+  const bool cand = idx != INT_MAX;
+  const T vv = cand ? v : (T)-INFINITY;
+  const T m = wave_max(vv);
+  const uint64_t tie = __ballot(cand && vv == m);
+  int win = INT_MAX;
+  if (tie != 0) {
+    if ((tie & (tie - 1)) == 0) win = read_lane(idx, __ffsll((unsigned long long)tie) - 1);
+    else win = wave_min((tie >> lane_id() & 1) ? idx : INT_MAX);
   }
-  MOE_ALL_STEPS(STEP_)
-#undef STEP_
+  v = tie != 0 ? m : (T)0;
+  idx = win;
 }
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) {
@@ -613,7 +648,7 @@ __device__ __forceinline__ void group_stage(const SelCfg& c, const Keys<FT, EPL>
     FT v = gsum; int idx = (lane < c.G && !(kept >> lane & 1)) ? lane : INT_MAX;
     wave_argmax(v, idx);
     kept |= uint64_t(1) << idx;
-    const FT lo = __shfl(gsum - gerr, idx);
+    const FT lo = read_lane(gsum - gerr, idx & 63);
     low = lo < low ? lo : low;
   }
   FT hi = (lane < c.G && !(kept >> lane & 1)) ? gsum + gerr : -INFINITY;
@@ -658,8 +693,8 @@ __device__ __forceinline__ void topk_stage(const SelCfg& c, const Keys<FT, EPL>&
 #pragma unroll
     for (int i = 0; i < EPL; ++i)
       if (i == slot) { oe = K.eps[i]; os = K.sc[i]; }
-    oe = __shfl(oe, owner);
-    os = __shfl(os, owner);
+    oe = read_lane(oe, owner);
+    os = read_lane(os, owner);
     if (lane == owner) taken |= 1u << slot;
     if (lane == j) { P.id = idx; P.sc = os; }
     if (!(prev_lo > v + oe) && j > 0) P.certain = false;
