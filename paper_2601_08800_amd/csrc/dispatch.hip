@@ -123,29 +123,35 @@ __global__ __launch_bounds__(256) void dispatch_place_kernel(
   inv[a] = pos;
 }
 
-// One wavefront per local expert: exclusive scan of the expert's row of counts
-// (lane l owns a contiguous run of sub-chunks), counts[e] = the row's total.
-__global__ __launch_bounds__(64) void dispatch_scan_kernel(int32_t* __restrict__ hist, int n_sub,
-                                                          int32_t* __restrict__ counts) {
-  const int lane = threadIdx.x, e = blockIdx.x;
+// One workgroup of four wavefronts per local expert: exclusive scan of the
+// expert's row of counts (thread i owns a contiguous run of sub-chunks; a scan over
+// the lanes of each wavefront, then over the four wavefront totals), counts[e] =
+// the row's total.  Integer sums: the result does not depend on the split.
+__global__ __launch_bounds__(256) void dispatch_scan_kernel(int32_t* __restrict__ hist, int n_sub,
+                                                           int32_t* __restrict__ counts) {
+  __shared__ int32_t wave_total[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, e = blockIdx.x;
   int32_t* row = hist + size_t(e) * n_sub;
-  const int per = (n_sub + 63) / 64;
-  const int s0 = lane * per, s1 = (s0 + per < n_sub) ? s0 + per : n_sub;
+  const int per = (n_sub + 255) / 256;
+  const int s0 = min(n_sub, tid * per), s1 = min(n_sub, s0 + per);
   int sum = 0;
   for (int sb = s0; sb < s1; ++sb) sum += row[sb];
-  int incl = sum;                               // inclusive scan over lanes
+  int incl = sum;                               // inclusive scan over the lanes of the wavefront
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const int o = __shfl_up(incl, off);
     if (lane >= off) incl += o;
   }
+  if (lane == 63) wave_total[wave] = incl;
+  __syncthreads();
   int run = incl - sum;
+  for (int w = 0; w < wave; ++w) run += wave_total[w];
   for (int sb = s0; sb < s1; ++sb) {
     const int c = row[sb];
     row[sb] = run;
     run += c;
   }
-  if (lane == 63) counts[e] = incl;
+  if (tid == 255) counts[e] = run;
 }
 
 // One wavefront per token: read the row once, write it to every local position.
@@ -357,7 +363,7 @@ hipError_t launch_dispatch(const moe_config& c, int T, const void* x, const int3
   const dim3 grid_idx((n_sub + 3) / 4), block_idx(256);
   MOE_LAUNCH(MOE_K_DISPATCH_HIST, dispatch_count_kernel, grid_idx, block_idx, 0, s, ids, A,
              c.expert_lo, E_loc, n_sub, ws.block_hist, inv);
-  MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_scan_kernel, dim3(E_loc), dim3(64), 0, s, ws.block_hist,
+  MOE_LAUNCH(MOE_K_DISPATCH_SCAN, dispatch_scan_kernel, dim3(E_loc), dim3(256), 0, s, ws.block_hist,
              n_sub, counts);
   MOE_LAUNCH(MOE_K_DISPATCH_SCATTER, dispatch_place_kernel, dim3((A + 255) / 256), block_idx, 0, s,
              ids, A, c.expert_lo, E_loc, n_sub, ws.block_hist, counts, offsets, perm, inv);
