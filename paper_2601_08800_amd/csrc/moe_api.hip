@@ -48,6 +48,7 @@ RouteWs carve_route(void* ws, int T, int E) {
   r.xnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * 4 * kGateMaxSplit);
   r.wnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(E) * 4);
   r.recheck = reinterpret_cast<int32_t*>(p + off);  off += align_up(size_t(T) * 4);
+  r.recheck_low = reinterpret_cast<float*>(p + off); off += align_up(size_t(T) * 4);
   r.bytes = off;
   return r;
 }

@@ -25,7 +25,8 @@ struct RouteWs {
   float* logits;       // [kGateMaxSplit][T,E] fast logits (fp32), one slab per K split
   float* xnorm2;       // [kGateMaxSplit][T] sum of squares of the token row, per K split
   float* wnorm2;       // [E] sum of squares of the gate row
-  int32_t* recheck;    // [T] token ids to re-score (bit 30 set: all experts)
+  int32_t* recheck;    // [T] token ids to re-score
+  float* recheck_low;  // [T] per listed token: smallest lower bound of its picks (NaN: not known)
   size_t bytes;
 };
 RouteWs carve_route(void* ws, int T, int E);

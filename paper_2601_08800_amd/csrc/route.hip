@@ -752,7 +752,8 @@ __global__ __launch_bounds__(256) void route_select_kernel(
     SelCfg c, int T, const float* __restrict__ logits, const float* __restrict__ logit_bias,
     const float* __restrict__ select_bias, const float* __restrict__ xnorm2,
     const float* __restrict__ wnorm2, int32_t* __restrict__ ids, float* __restrict__ w,
-    int32_t* __restrict__ counters, int32_t* __restrict__ recheck) {
+    int32_t* __restrict__ counters, int32_t* __restrict__ recheck,
+    float* __restrict__ recheck_low) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -774,6 +775,8 @@ __global__ __launch_bounds__(256) void route_select_kernel(
     // order of the list is irrelevant: every listed token is re-scored on its own
     const int slot = atomicAdd(&counters[0], 1);
     recheck[slot] = t;
+    // with the groups settled, the re-scoring starts from the picks found here
+    recheck_low[slot] = Gp.certain ? P.low : __builtin_nanf("");
   }
 }
 
@@ -793,7 +796,7 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     const float* __restrict__ logit_bias, const float* __restrict__ select_bias,
     const float* __restrict__ xnorm2, const float* __restrict__ wnorm2, int32_t* __restrict__ ids,
     float* __restrict__ w, const int32_t* __restrict__ counters,
-    const int32_t* __restrict__ recheck) {
+    const int32_t* __restrict__ recheck, const float* __restrict__ recheck_low) {
   __shared__ int xlist_all[4][EPL * 64];
   __shared__ double zx_all[4][EPL * 64];
   __shared__ float2 rint_all[4][EPL * 64];     // key intervals of the listed experts
@@ -916,10 +919,12 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
       group_stage<double, EPL>(c, D, lane, Gd);
       kept = Gd.kept;
     }
-    // phase 2: candidates of the top-k
+    // phase 2: candidates of the top-k.  The smallest lower bound of the fast picks
+    // comes from the selection pass unless the groups had to be settled here.
     const uint32_t elig = eligible_mask<EPL>(c, kept, lane);
     Picks<float> P;
-    topk_stage<float, EPL>(c, K, elig, lane, P);
+    P.low = recheck_low[li];
+    if (!(P.low == P.low)) topk_stage<float, EPL>(c, K, elig, lane, P);
     // Only experts whose upper bound reaches the smallest lower bound of a pick can
     // be among the picks.  Of those, an expert whose interval is apart from every
     // other's is ordered against all of them by its fast key already; the ones whose
@@ -1079,16 +1084,16 @@ void launch_select_and_recheck(const SelCfg& sc, const moe_config& c, int T, con
                                hipStream_t s) {
   MOE_LAUNCH(MOE_K_SELECT, route_select_kernel<EPL>, dim3((T + 3) / 4), dim3(256), 0, s, sc, T, logits,
                      logit_bias, select_bias, ws.xnorm2, ws.wnorm2, ids, w, ws.counters,
-                     ws.recheck);
+                     ws.recheck, ws.recheck_low);
   const int grid = T < 4096 ? (T + 3) / 4 : 1024;   // four tokens per workgroup at a time
   if (c.act_dtype == MOE_BF16)
     MOE_LAUNCH(MOE_K_RESCORE, (route_recheck_kernel<EPL, true>), dim3(grid), dim3(256), 0, s, sc,
                        c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
-                       ws.wnorm2, ids, w, ws.counters, ws.recheck);
+                       ws.wnorm2, ids, w, ws.counters, ws.recheck, ws.recheck_low);
   else
     MOE_LAUNCH(MOE_K_RESCORE, (route_recheck_kernel<EPL, false>), dim3(grid), dim3(256), 0, s, sc,
                        c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
-                       ws.wnorm2, ids, w, ws.counters, ws.recheck);
+                       ws.wnorm2, ids, w, ws.counters, ws.recheck, ws.recheck_low);
 }
 
 }  // namespace
