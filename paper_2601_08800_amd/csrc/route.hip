@@ -524,6 +524,7 @@ struct Groups {
   uint64_t kept;    // bit g: group g survives the group limit
   bool certain;     // the cut between kept and dropped groups holds for any keys within eps
   uint32_t need;    // bit per slot: the expert may be one of its group's group_score_n largest
+  uint64_t open;    // bit g: whether group g is kept depends on exact scores
 };
 
 template <typename FT>
@@ -656,6 +657,13 @@ __device__ __forceinline__ void group_stage(const SelCfg& c, const Keys<FT, EPL>
   Gp.kept = kept;
   Gp.certain = (c.Kg >= c.G) || (low > hi);
   Gp.need = need;
+  // A kept group whose lower bound clears every dropped group's upper bound stays
+  // kept whatever the exact keys are (only kept groups can outrank it), and a
+  // dropped group whose upper bound is below every kept group's lower bound stays
+  // dropped; the cut is open only among the others.
+  bool open = false;
+  if (lane < c.G) open = (kept >> lane & 1) ? !(gsum - gerr > hi) : !(gsum + gerr < low);
+  Gp.open = __ballot(open);
 }
 
 // Eligibility bits per slot: valid expert whose group is kept.
@@ -761,7 +769,7 @@ __global__ __launch_bounds__(256) void route_select_kernel(
   const float xn = token_norm(c, xnorm2, t);
   fast_keys<EPL>(c, logits + size_t(t) * c.E, logit_bias, select_bias, xn, wnorm2, lane, K);
   Groups<float> Gp;
-  Gp.kept = 0; Gp.certain = true; Gp.need = 0;
+  Gp.kept = 0; Gp.certain = true; Gp.need = 0; Gp.open = 0;
   if (c.G > 1) group_stage<float, EPL>(c, K, lane, Gp);
   Picks<float> P;
   topk_stage<float, EPL>(c, K, eligible_mask<EPL>(c, Gp.kept, lane), lane, P);
@@ -885,7 +893,7 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     Keys<float, EPL> K;
     Keys<double, EPL> D;
     Groups<float> Gf;
-    Gf.kept = 0; Gf.certain = true; Gf.need = 0;
+    Gf.kept = 0; Gf.certain = true; Gf.need = 0; Gf.open = 0;
     uint32_t exact = 0;          // slots of this lane that hold exact keys
     auto adopt = [&](uint32_t want) {   // pull exact logits into D
 #pragma unroll
@@ -912,9 +920,17 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     if (c.G > 1) group_stage<float, EPL>(c, K, lane, Gf);
     uint64_t kept = Gf.kept;
     if (c.G > 1 && !Gf.certain) {       // phase 1: settle the groups in fp64
-      const int n = make_list(Gf.need);
+      // exact keys only where they can matter: the possible largest members of the
+      // groups on whose scores the cut still depends.  The other groups keep their
+      // fast scores, which the intervals already order against every open group.
+      uint32_t want1 = 0;
+      const int gs = c.E / c.G;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i)
+        if ((Gf.need >> i & 1) && (Gf.open >> ((i * 64 + lane) / gs) & 1)) want1 |= 1u << i;
+      const int n = make_list(want1);
       exact_logits(t, n);
-      adopt(Gf.need);
+      adopt(want1);
       Groups<double> Gd;
       group_stage<double, EPL>(c, D, lane, Gd);
       kept = Gd.kept;
