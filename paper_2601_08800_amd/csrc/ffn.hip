@@ -845,17 +845,18 @@ __global__ __launch_bounds__(256) void ffn_skinny_kernel(
 
 // ------------------------------------------------------------ fp32 GEMM
 // Plain VALU kernel for the fp32 configuration: 64x64 tile, 16x16 threads,
-// 4x4 outputs per thread, K step 16.
+// 4x4 outputs per thread, K step 32; the next step's operands are fetched into
+// registers while the current step is computed from LDS.
 template <bool DUAL>
 __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ A,
                                                      const float* __restrict__ B0,
                                                      const float* __restrict__ B1,
                                                      float* __restrict__ C, int N, int K,
                                                      const int32_t* __restrict__ tiles) {
-  constexpr int TB = 64, TK = 16;
-  __shared__ float As[TK][TB + 4];
-  __shared__ float Bg[TK][TB + 4];
-  __shared__ float Bu[DUAL ? TK : 1][TB + 4];
+  constexpr int TB = 64, TK = 32, PER = TB * TK / 256;
+  __shared__ __align__(16) float As[TK][TB + 4];
+  __shared__ __align__(16) float Bg[TK][TB + 4];
+  __shared__ __align__(16) float Bu[DUAL ? TK : 1][TB + 4];
   const int n_ntiles = (N + TB - 1) / TB;
   const int mtile = blockIdx.x / n_ntiles, ntile = blockIdx.x % n_ntiles;
   if (mtile >= tiles[0]) return;
@@ -866,26 +867,39 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
   const float* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   float g[4][4] = {}, u[4][4] = {};
-  for (int k0 = 0; k0 < K; k0 += TK) {
-    for (int idx = threadIdx.x; idx < TB * TK; idx += 256) {
-      const int r = idx / TK, kk = idx % TK;
-      const int k = k0 + kk;
+  float ra[PER], rg[PER], ru[PER];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int idx = threadIdx.x + i * 256;
+      const int r = idx / TK, k = k0 + idx % TK;
       int ar = row0 + r; ar = ar < row1 ? ar : row1 - 1;
       int bn = n0 + r;   bn = bn < N ? bn : N - 1;
-      As[kk][r] = k < K ? A[size_t(ar) * K + k] : 0.f;
-      Bg[kk][r] = k < K ? Be0[size_t(bn) * K + k] : 0.f;
-      if (DUAL) Bu[kk][r] = k < K ? Be1[size_t(bn) * K + k] : 0.f;
+      ra[i] = k < K ? A[size_t(ar) * K + k] : 0.f;
+      rg[i] = k < K ? Be0[size_t(bn) * K + k] : 0.f;
+      if (DUAL) ru[i] = k < K ? Be1[size_t(bn) * K + k] : 0.f;
+    }
+  };
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += TK) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int idx = threadIdx.x + i * 256;
+      const int r = idx / TK, kk = idx % TK;
+      As[kk][r] = ra[i];
+      Bg[kk][r] = rg[i];
+      if (DUAL) Bu[kk][r] = ru[i];
     }
     __syncthreads();
+    if (k0 + TK < K) fetch(k0 + TK);
 #pragma unroll
     for (int kk = 0; kk < TK; ++kk) {
-      float a[4], bg[4], bu[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        a[i] = As[kk][ty * 4 + i];
-        bg[i] = Bg[kk][tx * 4 + i];
-        bu[i] = DUAL ? Bu[kk][tx * 4 + i] : 0.f;
-      }
+      // rows of the LDS tiles are 68 floats, so groups of four stay 16-byte aligned
+      const float4 a4 = *reinterpret_cast<const float4*>(&As[kk][ty * 4]);
+      const float4 g4 = *reinterpret_cast<const float4*>(&Bg[kk][tx * 4]);
+      const float4 u4 = DUAL ? *reinterpret_cast<const float4*>(&Bu[kk][tx * 4]) : make_float4(0.f, 0.f, 0.f, 0.f);
+      const float a[4] = {a4.x, a4.y, a4.z, a4.w}, bg[4] = {g4.x, g4.y, g4.z, g4.w},
+                  bu[4] = {u4.x, u4.y, u4.z, u4.w};
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
