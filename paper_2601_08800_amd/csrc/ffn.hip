@@ -1000,6 +1000,34 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
              (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, tiles2, 1);
 }
 
+// Between the two: a handful of rows per expert.  GEMM-1 (K = H long) streams its
+// weights fastest through the LDS rings of the tall-tile kernel even when a tile
+// holds one or two row blocks; GEMM-2 (K = I_loc short, N = H wide) is best as
+// many small weight-streaming workgroups.  Each kernel gets its own tile table.
+void launch_mixed(const moe_config& c, int n_experts, const void* xs, const int32_t* offsets,
+                  int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
+                  void* ys, const FfnWs& ws, hipStream_t s) {
+  const int H = c.hidden, I = c.inter_local;
+  const int bm = 160, bm2 = 32;
+  const int max_mt = rows_capacity / bm + n_experts;
+  const int max_mt2 = rows_capacity / bm2 + n_experts;
+  const int cap = max_mt2 < ws.max_tiles ? max_mt2 : ws.max_tiles;
+  MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(2), dim3(256), 0, s, offsets, n_experts, bm,
+             rows_capacity, ws.tiles, cap, 1, bm2, ws.tiles2);
+  const int nt1 = (I + 127) / 128, nt2 = (H + 63) / 64;
+  constexpr int lds = 160 * 1024;
+  const int g1 = (max_mt * nt1 + 7) / 8 * 8;
+  auto k1 = ffn_gemm8w_kernel<true>;
+  static uint64_t opted1 = 0;
+  lds_opt_in(reinterpret_cast<const void*>(k1), lds, opted1);
+  MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
+             static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
+             static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
+  MOE_LAUNCH(MOE_K_FFN_GEMM2, (ffn_skinny_kernel<false, false>), dim3(size_t(max_mt2) * nt2), dim3(256),
+             0, s, static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr,
+             (const float*)nullptr, (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles2);
+}
+
 }  // namespace
 
 hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
@@ -1032,14 +1060,17 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
     launch_skinny<true>(MOE_FFN_ARGS);
   } else if (fp8) {
     launch_mfma_pair<32, 128, 32, 32, 256, 64, true>(MOE_FFN_ARGS);
-  } else if (avg <= 32 && H % 64 == 0 && I % 64 == 0) {
-    launch_skinny<false>(MOE_FFN_ARGS);
+  } else if (H % BK == 0 && I % BK == 0) {
+    // measured on the 128-expert layer (hidden 2048, I 768): with at most two rows
+    // per expert the weight-streaming kernel wins both GEMMs, from about twelve on
+    // the tall-tile kernel does, in between each takes the GEMM it is better at
+    if (avg <= 2) launch_skinny<false>(MOE_FFN_ARGS);
+    else if (avg <= 12) launch_mixed(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
+    else launch_mfma256(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
   } else if (avg <= 32) {
     launch_mfma_pair<32, 128, 32, 32, 256, 64, false>(MOE_FFN_ARGS);
   } else if (avg <= 64) {
     launch_mfma_pair<64, 128, 64, 32, 256, 64, false>(MOE_FFN_ARGS);
-  } else if (H % BK == 0 && I % BK == 0) {
-    launch_mfma256(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
   } else {
     launch_mfma_pair<128, 64, 64, 32, 128, 64, false>(MOE_FFN_ARGS);
   }

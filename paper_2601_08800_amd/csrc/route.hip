@@ -1126,10 +1126,15 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   sc.G = c.n_groups; sc.Kg = c.topk_groups; sc.gn = c.group_score_n; sc.scale = c.routed_scale;
   sc.chain_err = 0.f; sc.have_norms = 0; sc.nsplit = 1; sc.T = T;
   const int epl = (E + 63) / 64;
-  // decode-sized batches: the exact gate costs T*E*H fp64 fused multiply-adds, a
-  // few microseconds up to about 2^28 of them: one kernel does the whole stage
-  // (a workgroup per token: not for long batches of tiny layers)
-  const bool small = size_t(T) * E * H <= (size_t(1) << 28) && T <= 4096;
+  // decode-sized batches: the exact gate costs T*E*H fp64 fused multiply-adds,
+  // about 0.24 us per 2^20 of them, in one kernel for the whole stage (a workgroup
+  // per token: not for long batches of tiny layers).  The bf16 pipeline of four
+  // kernels takes 45-50 us at these sizes (measured on the 128-expert layer, hidden
+  // 2048: 51 us exact against 46 us tiled at 768 tokens), which puts the crossover
+  // near 5 * 2^25; the fp32 pipeline starts with an fp64 VALU gate of its own and is
+  // never faster below 2^28.
+  const size_t small_limit = bf16 ? size_t(5) << 25 : size_t(1) << 28;
+  const bool small = size_t(T) * E * H <= small_limit && T <= 4096;
   if (!logits_in && small) {
     if (epl <= 1) launch_route_exact<1>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
     else if (epl <= 2) launch_route_exact<2>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
