@@ -230,12 +230,35 @@ def main():
         out["hip_graph_replay"] = {"error": str(exc)[:200]}
 
     out["next_rows"] = next_rows(moe, L, w, x, a_loc, tokens_local, max(args.steps, 5))
+    if forced is not None:
+        out["route_separately"] = route_separately(moe, L, x, max(args.steps, 5))
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x_np, gate, experts, shared, forced_np,
                                            args.cpu_seconds)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def route_separately(moe, L, x, steps):
+    """Workloads with forced routing skip the gate inside the timed step; the
+    route of the same layer (normal gate on the same tokens) is timed here on
+    its own: kernel durations from HIP events, per call."""
+    import torch
+    for _ in range(3):
+        L.route(x)
+    torch.cuda.synchronize()
+    moe.moe_profile_filter(None)
+    moe.moe_profile_enable(16 * steps + 16)
+    for _ in range(steps):
+        L.route(x)
+    torch.cuda.synchronize()
+    rec = moe.moe_profile_read()
+    moe.moe_profile_enable(0)
+    res = {name: round(ms * 1e3 / steps, 2) for name, (ms, n) in rec.items()}
+    res["us"] = round(sum(res.values()), 2)
+    res["tokens_rescored_fp64"] = int(L.ws[:4].view(torch.int32).item())
+    return res
 
 
 def next_rows(moe, L, w, x, a_loc, tokens_local, steps):
