@@ -1080,6 +1080,119 @@ __global__ __launch_bounds__(1024) void route_exact_kernel(
   }
 }
 
+// ---------- few tokens, long gate rows: exact logits and selection as two kernels
+// When a token's E*H multiply-adds are many (256 experts x hidden 7168), one
+// workgroup per token is a chain of sixteen dependent load rounds per wavefront.
+// Here a workgroup of four wavefronts takes sixteen experts of one token (a
+// wavefront: four gate rows, eight 16-byte pieces per lane and row in flight), so
+// a token is shared out over E/16 workgroups and the fp64 logits go to the
+// workspace; a second kernel, one wavefront per token, selects on the fp64 keys.
+template <bool BF16>
+__global__ __launch_bounds__(256) void gate_exact_kernel(
+    int H, int E, const void* __restrict__ x, const void* __restrict__ gate_w,
+    const float* __restrict__ logit_bias, double* __restrict__ zx, int32_t* __restrict__ counters) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.y;
+  if (blockIdx.x == 0 && t == 0 && threadIdx.x < 64) counters[threadIdx.x] = 0;   // nothing is re-scored
+  constexpr int CB = 4, U = 8;
+  const int e0 = (blockIdx.x * 4 + wave) * CB;
+  if (e0 >= E) return;
+  const size_t eb = BF16 ? 2 : 4;
+  const char* xrow = static_cast<const char*>(x) + size_t(t) * H * eb;
+  const int n16 = int(H * eb / 16);
+  double acc[CB];
+  const char* wrow[CB];
+#pragma unroll
+  for (int i = 0; i < CB; ++i) {
+    acc[i] = 0.0;
+    wrow[i] = static_cast<const char*>(gate_w) + size_t(min(e0 + i, E - 1)) * H * eb;
+  }
+  for (int p0 = 0; p0 < n16; p0 += 64 * U) {
+    uint4 a[U], b[CB][U];
+    bool in[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int p = p0 + u * 64 + lane;
+      in[u] = p < n16;
+      p = in[u] ? p : n16 - 1;
+      a[u] = *reinterpret_cast<const uint4*>(xrow + size_t(p) * 16);
+#pragma unroll
+      for (int i = 0; i < CB; ++i) b[i][u] = *reinterpret_cast<const uint4*>(wrow[i] + size_t(p) * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < CB; ++i) {
+        const double d = piece_dot64<BF16>(a[u], b[i][u], 0.0);
+        acc[i] += in[u] ? d : 0.0;
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < CB; ++i) {
+    double z = wave_sum(acc[i]);
+    if (e0 + i < E && lane == 0) {
+      if (logit_bias) z += (double)logit_bias[e0 + i];
+      zx[size_t(t) * E + e0 + i] = z;
+    }
+  }
+}
+
+template <int EPL>
+__global__ __launch_bounds__(256) void select_exact_kernel(
+    SelCfg c, int T, const double* __restrict__ zx, const float* __restrict__ select_bias,
+    int32_t* __restrict__ ids, float* __restrict__ w) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  Keys<double, EPL> D;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int e = i * 64 + lane;
+    D.key[i] = -INFINITY; D.sc[i] = 0.0; D.eps[i] = 0.0;
+    if (e < c.E) {
+      const double z = zx[size_t(t) * c.E + e];
+      if (c.score_fn == MOE_SCORE_SOFTMAX) {
+        D.key[i] = z; D.sc[i] = z;
+      } else {
+        const double sg = 1.0 / (1.0 + exp(-z));
+        D.sc[i] = sg;
+        D.key[i] = sg + (select_bias ? (double)select_bias[e] : 0.0);
+      }
+    }
+  }
+  uint64_t kept = 0;
+  if (c.G > 1) {
+    Groups<double> Gd;
+    group_stage<double, EPL>(c, D, lane, Gd);
+    kept = Gd.kept;
+  }
+  const uint32_t elig = eligible_mask<EPL>(c, kept, lane);
+  Picks<double> Q;
+  topk_stage<double, EPL>(c, D, elig, lane, Q);
+  const double wt = pick_weight<double, EPL>(c, D, Q, lane);
+  if (lane < c.k) {
+    ids[size_t(t) * c.k + lane] = Q.id;
+    w[size_t(t) * c.k + lane] = (float)wt;
+  }
+}
+
+template <int EPL>
+void launch_route_exact2(const SelCfg& sc, const moe_config& c, int T, const void* x,
+                         const void* gate_w, const float* logit_bias, const float* select_bias,
+                         int32_t* ids, float* w, const RouteWs& ws, hipStream_t s) {
+  // the logits area holds kGateMaxSplit >= 2 floats per (token, expert): room for one double
+  double* zx = reinterpret_cast<double*>(ws.logits);
+  const dim3 grid((c.n_experts + 15) / 16, T);
+  if (c.act_dtype == MOE_BF16)
+    MOE_LAUNCH(MOE_K_GATE_GEMM, gate_exact_kernel<true>, grid, dim3(256), 0, s, c.hidden, c.n_experts, x,
+               gate_w, logit_bias, zx, ws.counters);
+  else
+    MOE_LAUNCH(MOE_K_GATE_GEMM, gate_exact_kernel<false>, grid, dim3(256), 0, s, c.hidden, c.n_experts, x,
+               gate_w, logit_bias, zx, ws.counters);
+  MOE_LAUNCH(MOE_K_SELECT, select_exact_kernel<EPL>, dim3((T + 3) / 4), dim3(256), 0, s, sc, T, zx,
+             select_bias, ids, w);
+}
+
 template <int EPL>
 void launch_route_exact(const SelCfg& sc, const moe_config& c, int T, const void* x,
                         const void* gate_w, const float* logit_bias, const float* select_bias,
@@ -1135,6 +1248,19 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   // never faster below 2^28.
   const size_t small_limit = bf16 ? size_t(5) << 25 : size_t(1) << 28;
   const bool small = size_t(T) * E * H <= small_limit && T <= 4096;
+  // long gate rows and few tokens: the same arithmetic as two kernels.  Measured on
+  // 256 experts x hidden 7168: 37 / 53 / 81 us at 16 / 64 / 128 tokens, where one
+  // workgroup per token takes 84 us and the bf16 pipeline 92 us; the fp64 work grows
+  // with the token count (135 us at 256), so the switch back sits at 2^28.
+  const bool long_rows = size_t(E) * H > (size_t(1) << 19) && T <= 4096 &&
+                         size_t(T) * E * H <= (size_t(1) << 28);
+  if (!logits_in && long_rows) {
+    if (epl <= 1) launch_route_exact2<1>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
+    else if (epl <= 2) launch_route_exact2<2>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
+    else if (epl <= 4) launch_route_exact2<4>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
+    else launch_route_exact2<8>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
+    return hipGetLastError();
+  }
   if (!logits_in && small) {
     if (epl <= 1) launch_route_exact<1>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
     else if (epl <= 2) launch_route_exact<2>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);

@@ -137,6 +137,36 @@ def test_route_tiled_gate_matches_oracle(name):
     assert 0 <= n_re <= w.T
 
 
+# Few tokens, long gate rows (E*H > 2^19): exact logits and selection run as two
+# kernels, a token's experts shared out over several workgroups.  Group-limited
+# sigmoid at the C4 gate shape, soft-max with 512 and with an odd number of
+# experts, fp32 inputs; one token, and token counts that are no multiple of four.
+LONG_ROWS = {
+    "c4_gate_1_token": gen.CONFIGS["c4"].replace(name="c4_gate_1_token", T=1, I=128, shared_expert=False),
+    "c4_gate_67_tokens": gen.CONFIGS["c4"].replace(name="c4_gate_67_tokens", T=67, I=128,
+                                                   shared_expert=False),
+    "softmax_512_experts": gen.CONFIGS["c3"].replace(name="softmax_512_experts", T=130, E=512, H=2048,
+                                                     I=64, expert_lo=0, expert_hi=8),
+    "softmax_130_experts": gen.CONFIGS["c3"].replace(name="softmax_130_experts", T=5, E=130, H=8192,
+                                                     I=64, expert_lo=0, expert_hi=8),
+    "f32_72_experts": gen.CONFIGS["c1"].replace(name="f32_72_experts", T=130, E=72, H=8192, I=64, k=4),
+}
+
+
+@pytest.mark.parametrize("name", list(LONG_ROWS))
+def test_route_long_gate_rows_matches_oracle(name):
+    w = LONG_ROWS[name]
+    assert w.E * w.H > 2 ** 19 and w.T * w.E * w.H <= 2 ** 28
+    print("case", name, flush=True)
+    x, gate = gen.make_x(w), gen.make_gate(w)
+    L = make_layer(w, {"gate": gate, "experts": gen.make_local_experts(w), "shared": None})
+    L.route(dev(x))
+    torch.cuda.synchronize()
+    assert int(L.ws[:4].view(torch.int32).item()) == 0          # exact keys: nothing to re-score
+    ids_ref, w_ref, margin = oracle_route(w, x, gate)
+    check_routing(host(L.topk_ids), host(L.topk_w), ids_ref, w_ref, margin, w.routed_scale, name)
+
+
 @pytest.mark.parametrize("E,k,score,G,Kg,gn", [
     (8, 2, "softmax", 1, 1, 0), (64, 6, "softmax", 1, 1, 0), (100, 8, "softmax", 1, 1, 0),
     (128, 8, "softmax", 1, 1, 0), (256, 8, "sigmoid", 8, 4, 2), (256, 8, "sigmoid", 1, 1, 0),
