@@ -797,7 +797,12 @@ __global__ __launch_bounds__(256) void route_select_kernel(
 // Experts outside those sets keep their fast keys: by construction they cannot
 // change either decision.  A wavefront's candidate list and exact logits live
 // in its own slice of LDS; LDS operations of one wavefront execute in order.
-template <int EPL, bool BF16>
+// COOP (short lists: few tokens in the batch): one token per workgroup.  The four
+// wavefronts run the same selection steps on the same data (so their control
+// flow is identical and the barriers below are reached by all of them) and share
+// out each exact dot product, a quarter of the token row each: the chain of
+// dependent load rounds, which is all this kernel's time, is four times shorter.
+template <int EPL, bool BF16, bool COOP>
 __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     SelCfg c, int H, const void* __restrict__ x, const void* __restrict__ gate_w,
     const float* __restrict__ logits_in, const float* __restrict__ logits,
@@ -808,6 +813,7 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
   __shared__ int xlist_all[4][EPL * 64];
   __shared__ double zx_all[4][EPL * 64];
   __shared__ float2 rint_all[4][EPL * 64];     // key intervals of the listed experts
+  __shared__ double part_all[COOP ? 4 : 1][4]; // COOP: partial dot products of the wavefronts
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int* const xlist = xlist_all[wave];
   double* const zx = zx_all[wave];
@@ -845,7 +851,8 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
       // U pieces per lane and expert in flight (the tail pieces are clamped to the
       // last one and masked out of the sum)
       constexpr int U = 4;
-      for (int p0 = 0; p0 < n16; p0 += 64 * U) {
+      // COOP: wavefront w walks the pieces w*64*U .. of every run of 4*64*U
+      for (int p0 = COOP ? wave * 64 * U : 0; p0 < n16; p0 += (COOP ? 4 : 1) * 64 * U) {
         uint4 a[U], b[CB][U];
         bool in[U];
 #pragma unroll
@@ -865,12 +872,31 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
             acc[i] += in[u] ? d : 0.0;
           }
       }
+      if constexpr (COOP) {
+        // the four partial sums of each expert, added in wavefront order by everyone
 #pragma unroll
-      for (int i = 0; i < CB; ++i) {
-        double z = wave_sum(acc[i]);
-        if (q0 + i < n && lane == 0) {
-          if (logit_bias) z += (double)logit_bias[ex[i]];
-          zx[ex[i]] = z;
+        for (int i = 0; i < CB; ++i) {
+          const double zp = wave_sum(acc[i]);
+          if (lane == 0) part_all[wave][i] = zp;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+          double z = ((part_all[0][i] + part_all[1][i]) + part_all[2][i]) + part_all[3][i];
+          if (q0 + i < n && lane == 0) {
+            if (logit_bias) z += (double)logit_bias[ex[i]];
+            zx[ex[i]] = z;
+          }
+        }
+        __syncthreads();                    // before the next batch overwrites the partial sums
+      } else {
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+          double z = wave_sum(acc[i]);
+          if (q0 + i < n && lane == 0) {
+            if (logit_bias) z += (double)logit_bias[ex[i]];
+            zx[ex[i]] = z;
+          }
         }
       }
     }
@@ -888,7 +914,8 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     return n;
   };
 
-  for (int li = blockIdx.x * 4 + wave; li < n_list; li += gridDim.x * 4) {
+  for (int li = COOP ? int(blockIdx.x) : int(blockIdx.x) * 4 + wave; li < n_list;
+       li += COOP ? int(gridDim.x) : int(gridDim.x) * 4) {
     const int t = recheck[li];
     Keys<float, EPL> K;
     Keys<double, EPL> D;
@@ -980,7 +1007,7 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
     Picks<double> Q;
     topk_stage<double, EPL>(c, D, elig, lane, Q);
     const double wt = pick_weight<double, EPL>(c, D, Q, lane);
-    if (lane < c.k) {
+    if (lane < c.k && (!COOP || wave == 0)) {
       ids[size_t(t) * c.k + lane] = Q.id;
       w[size_t(t) * c.k + lane] = (float)wt;
     }
@@ -1214,15 +1241,20 @@ void launch_select_and_recheck(const SelCfg& sc, const moe_config& c, int T, con
   MOE_LAUNCH(MOE_K_SELECT, route_select_kernel<EPL>, dim3((T + 3) / 4), dim3(256), 0, s, sc, T, logits,
                      logit_bias, select_bias, ws.xnorm2, ws.wnorm2, ids, w, ws.counters,
                      ws.recheck, ws.recheck_low);
-  const int grid = T < 4096 ? (T + 3) / 4 : 1024;   // four tokens per workgroup at a time
-  if (c.act_dtype == MOE_BF16)
-    MOE_LAUNCH(MOE_K_RESCORE, (route_recheck_kernel<EPL, true>), dim3(grid), dim3(256), 0, s, sc,
-                       c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
-                       ws.wnorm2, ids, w, ws.counters, ws.recheck, ws.recheck_low);
-  else
-    MOE_LAUNCH(MOE_K_RESCORE, (route_recheck_kernel<EPL, false>), dim3(grid), dim3(256), 0, s, sc,
-                       c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,
-                       ws.wnorm2, ids, w, ws.counters, ws.recheck, ws.recheck_low);
+  // short batches have short lists: a workgroup per listed token, its wavefronts
+  // sharing each dot product; otherwise four tokens per workgroup at a time
+  const bool coop = T <= 1024 && !logits_in;
+  const int grid = coop ? T : (T < 4096 ? (T + 3) / 4 : 1024);
+#define MOE_RECHECK(BF, CO)                                                                       \
+  MOE_LAUNCH(MOE_K_RESCORE, (route_recheck_kernel<EPL, BF, CO>), dim3(grid), dim3(256), 0, s, sc, \
+             c.hidden, x, gate_w, logits_in, logits, logit_bias, select_bias, ws.xnorm2,          \
+             ws.wnorm2, ids, w, ws.counters, ws.recheck, ws.recheck_low)
+  if (c.act_dtype == MOE_BF16) {
+    if (coop) MOE_RECHECK(true, true); else MOE_RECHECK(true, false);
+  } else {
+    if (coop) MOE_RECHECK(false, true); else MOE_RECHECK(false, false);
+  }
+#undef MOE_RECHECK
 }
 
 }  // namespace
