@@ -44,8 +44,8 @@ RouteWs carve_route(void* ws, int T, int E) {
   char* p = static_cast<char*>(ws);
   size_t off = 0;
   r.counters = reinterpret_cast<int32_t*>(p + off); off += kRouteCounterBytes;
-  r.logits = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * E * 4 * kGateMaxSplit);
-  r.xnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * 4 * kGateMaxSplit);
+  r.logits = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * E * 4 * gate_split_cap(T, E));
+  r.xnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * 4 * gate_split_cap(T, E));
   r.wnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(E) * 4);
   r.recheck = reinterpret_cast<int32_t*>(p + off);  off += align_up(size_t(T) * 4);
   r.recheck_low = reinterpret_cast<float*>(p + off); off += align_up(size_t(T) * 4);

@@ -19,11 +19,22 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 // route
 constexpr int kRouteCounterBytes = 256;       // [0]=tokens re-scored in fp64
 constexpr int kGateMaxSplit = 4;              // K splits of the gate GEMM when few tokens leave CUs idle
+constexpr int kGateWgTarget = 512;            // workgroups the gate GEMM aims at: two per CU
+constexpr int kGateTileM = 64, kGateTileN = 128;
+// K splits the gate GEMM can use at most on a T x E grid of tiles (its workspace
+// holds that many slabs).  Never below two: the exact two-kernel route keeps one
+// double per (token, expert) in the same area.
+inline int gate_split_cap(int T, int E) {
+  const long blocks = long((T + kGateTileM - 1) / kGateTileM) * ((E + kGateTileN - 1) / kGateTileN);
+  int n = 1;
+  while (n < kGateMaxSplit && blocks * n * 2 <= kGateWgTarget) n *= 2;
+  return n < 2 ? 2 : n;
+}
 constexpr int kGateChainSteps = 1;            // K-steps of 64 per fp32 accumulation chain
 struct RouteWs {
   int32_t* counters;   // [64]
-  float* logits;       // [kGateMaxSplit][T,E] fast logits (fp32), one slab per K split
-  float* xnorm2;       // [kGateMaxSplit][T] sum of squares of the token row, per K split
+  float* logits;       // [gate_split_cap][T,E] fast logits (fp32), one slab per K split
+  float* xnorm2;       // [gate_split_cap][T] sum of squares of the token row, per K split
   float* wnorm2;       // [E] sum of squares of the gate row
   int32_t* recheck;    // [T] token ids to re-score
   float* recheck_low;  // [T] per listed token: smallest lower bound of its picks (NaN: not known)

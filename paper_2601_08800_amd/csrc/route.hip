@@ -238,8 +238,7 @@ __global__ __launch_bounds__(256) void gate_f64_kernel(const void* __restrict__ 
 // so that the 16 lanes the LDS serves per cycle fall on 16 different 16-byte
 // columns.
 // K of the gate GEMM is split until about this many workgroups run (2 per CU)
-constexpr int kGateWgTarget = 512;
-constexpr int GBM = 64, GBN = 128, GBK = 64;
+constexpr int GBM = kGateTileM, GBN = kGateTileN, GBK = 64;
 
 __device__ __forceinline__ int swz(int row, int piece) {
   return row * 8 + (piece ^ ((row >> 1) & 7));
@@ -1207,7 +1206,7 @@ template <int EPL>
 void launch_route_exact2(const SelCfg& sc, const moe_config& c, int T, const void* x,
                          const void* gate_w, const float* logit_bias, const float* select_bias,
                          int32_t* ids, float* w, const RouteWs& ws, hipStream_t s) {
-  // the logits area holds kGateMaxSplit >= 2 floats per (token, expert): room for one double
+  // the logits area holds at least two floats per (token, expert): room for one double
   double* zx = reinterpret_cast<double*>(ws.logits);
   const dim3 grid((c.n_experts + 15) / 16, T);
   if (c.act_dtype == MOE_BF16)
@@ -1317,7 +1316,8 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
       const int blocks = ((T + GBM - 1) / GBM) * ((E + GBN - 1) / GBN);
       const int ksteps = (H + GBK - 1) / GBK;
       int nsplit = 1;
-      while (nsplit < kGateMaxSplit && blocks * nsplit * 2 <= kGateWgTarget && ksteps / (nsplit * 2) >= 8) nsplit *= 2;
+      const int cap = gate_split_cap(T, E);
+      while (nsplit < cap && blocks * nsplit * 2 <= kGateWgTarget && ksteps / (nsplit * 2) >= 8) nsplit *= 2;
       const dim3 grid((T + GBM - 1) / GBM, (E + GBN - 1) / GBN, nsplit);
       if (H % GBK == 0) {
         // two stages (48 KB): three workgroups share a CU, which measured faster than
