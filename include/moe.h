@@ -153,6 +153,11 @@ moe_status moe_dispatch_shard(const moe_config* cfg, int32_t T, const void* x,
  *   w_gate, w_up [n, I_loc, H]   w_down [n, H, I_loc]   weight dtype
  *   s_gate, s_up [n, I_loc/128, ceil(H/128)]  s_down [n, ceil(H/128), I_loc/128]
  *           fp32 block scales, required for MOE_FP8_E4M3_B128, else NULL
+ *           (the weight is code * scale; with more than twelve rows per expert to
+ *           expect, rows_capacity / n_experts_here > 12, that product is rounded
+ *           to bf16 before the matrix instruction, otherwise the scale multiplies
+ *           the fp32 partial sum of its 128-deep block: both within the stated
+ *           fp8 tolerance of the exact product)
  *   ys      out [rows_capacity, H] act dtype
  * rows_capacity bounds offsets[n]; rows beyond offsets[n] are not touched.
  * The shared expert is the same call with n_experts_here = 1, offsets = {0,T},

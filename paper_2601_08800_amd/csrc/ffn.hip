@@ -360,12 +360,28 @@ __device__ __forceinline__ void wait_vmcnt() {
 // moves whole cache lines.  (A K step of 32 would allow four stages for the tall
 // tiles too, but its 64-byte row pieces halve the efficiency of the load path:
 // measured 8 % slower on the 256-row tiles.)
-template <int NB> struct Ring {
+// Eight e4m3 codes -> eight bf16 values of code * scale (exact widening to fp32,
+// one fp32 multiply, round to nearest even).
+__device__ __forceinline__ uint4 widen_scaled(uint2 c, float sc) {
+  const f32x2 p0 = __builtin_amdgcn_cvt_pk_f32_fp8(c.x, false), p1 = __builtin_amdgcn_cvt_pk_f32_fp8(c.x, true);
+  const f32x2 p2 = __builtin_amdgcn_cvt_pk_f32_fp8(c.y, false), p3 = __builtin_amdgcn_cvt_pk_f32_fp8(c.y, true);
+  uint4 r;
+  asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r.x) : "v"(p0[0] * sc), "v"(p0[1] * sc));
+  asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r.y) : "v"(p1[0] * sc), "v"(p1[1] * sc));
+  asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r.z) : "v"(p2[0] * sc), "v"(p2[1] * sc));
+  asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r.w) : "v"(p3[0] * sc), "v"(p3[1] * sc));
+  return r;
+}
+
+// F8: the weight tile holds e4m3 codes (64-byte rows: four pieces), widened to
+// bf16 on the way from LDS to the matrix unit.
+template <int NB, bool F8 = false> struct Ring {
   static constexpr int kBK = 64;
-  static constexpr int kPPR = kBK / 8;                              // 16-byte pieces per row
+  static constexpr int kPPR = kBK / 8;                              // 16-byte pieces per activation row
+  static constexpr int kPPRB = F8 ? kBK / 16 : kBK / 8;             // ... per weight row
   static constexpr int kARows = NB * 32;
   static constexpr int kASlots = kARows * kPPR;                     // 16-byte slots of an A stage
-  static constexpr int kBSlots = 256 * kPPR;                        // ... of a B stage
+  static constexpr int kBSlots = 256 * kPPRB;                       // ... of a B stage
   static constexpr int kLds = 160 * 1024;
   static constexpr int kFit = kLds / ((kASlots + kBSlots) * 16);
   static constexpr int kSB = kFit > 4 ? 4 : kFit;                   // weight stages
@@ -374,19 +390,28 @@ template <int NB> struct Ring {
   static constexpr int kSA = kSB + (kMore > MOE_RING_EXTRA_A ? MOE_RING_EXTRA_A : kMore);
 };
 
-template <bool DUAL, int NB, int WM>
+// F8: Be0 / Be1 point at e4m3 codes, Se0 / Se1 at the expert's block scales of
+// the 128-row block this wavefront's weight rows lie in ([K/128] values).  The
+// scaled weight code * scale is rounded to bf16 before the MFMA (the exact
+// per-block scale would need a second set of accumulators).
+template <bool DUAL, int NB, int WM, bool F8>
 __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
-                                            const uint16_t* __restrict__ Be0,
-                                            const uint16_t* __restrict__ Be1,
+                                            const char* __restrict__ Be0,
+                                            const char* __restrict__ Be1,
+                                            const float* __restrict__ Se0,
+                                            const float* __restrict__ Se1,
                                             uint16_t* __restrict__ C, int N, int K, int row0,
                                             int row1, int n0, uint4* smem, int wave) {
   constexpr int NBW = NB - WM * 4 < 0 ? 0 : (NB - WM * 4 > 4 ? 4 : NB - WM * 4);
-  constexpr int SA = Ring<NB>::kSA, SB = Ring<NB>::kSB;
-  constexpr int KS = Ring<NB>::kBK;                  // K step
-  constexpr int PPR = Ring<NB>::kPPR;                // pieces per LDS row: 8 or 4
+  constexpr int SA = Ring<NB, F8>::kSA, SB = Ring<NB, F8>::kSB;
+  constexpr int KS = Ring<NB, F8>::kBK;              // K step
+  constexpr int PPR = Ring<NB, F8>::kPPR;            // pieces per activation row in LDS
+  constexpr int PPRB = Ring<NB, F8>::kPPRB;          // pieces per weight row in LDS
   constexpr int RPI = 64 / PPR;                      // rows filled by one load instruction
-  constexpr int AS = Ring<NB>::kASlots;              // slots of an A stage
-  constexpr int BS = Ring<NB>::kBSlots;              // slots of a B stage
+  constexpr int RPIB = 64 / PPRB;
+  constexpr int WB = F8 ? 1 : 2;                     // bytes per weight element
+  constexpr int AS = Ring<NB, F8>::kASlots;          // slots of an A stage
+  constexpr int BS = Ring<NB, F8>::kBSlots;          // slots of a B stage
   uint4* const ringA = smem;
   uint4* const ringB = smem + SA * AS;
   const int lane = threadIdx.x & 63;
@@ -399,6 +424,9 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   auto slot = [&](int row, int piece) {
     return row * PPR + (piece ^ (PPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3));
   };
+  auto slot_b = [&](int row, int piece) {
+    return row * PPRB + (piece ^ (PPRB == 8 ? (row >> 1) & 7 : (row >> 2) & 3));
+  };
   // loads: a wavefront instruction fills 64 consecutive slots = RPI rows.  Row
   // group rg = q*8 + wave; lane l -> row l/PPR, and it fetches the piece that
   // belongs in slot l%PPR of that row: (l%PPR) ^ ((rg*4 + l/16) & (PPR-1)).
@@ -406,10 +434,10 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   constexpr int AGROUPS = NB * 32 / RPI;
   constexpr int NAQ = AGROUPS / 8;                   // full rounds of 8 wavefronts
   constexpr int AREM = AGROUPS % 8;                  // wavefronts 0..AREM-1 load one more
-  constexpr int NBQ = 256 / RPI / 8;                 // weight row groups per wavefront
+  constexpr int NBQ = 256 / RPIB / 8;                // weight row groups per wavefront
   const int lrow = lane / PPR;
   const uint16_t* asrc[NAQ + 1];
-  const uint16_t* bsrc[NBQ];
+  const char* bsrc[NBQ];
 #pragma unroll
   for (int q = 0; q < NAQ + 1; ++q) {
     const int rg = q * 8 + wave;
@@ -421,12 +449,12 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
 #pragma unroll
   for (int q = 0; q < NBQ; ++q) {
     const int rg = q * 8 + wave;
-    const int piece = (lane % PPR) ^ ((rg * 4 + (lane >> 4)) & (PPR - 1));
-    const int br = rg * RPI + lrow;
-    const uint16_t* base = (DUAL && br >= 128) ? Be1 : Be0;
+    const int piece = (lane % PPRB) ^ ((rg * 4 + (lane >> 4)) & (PPRB - 1));
+    const int br = rg * RPIB + lane / PPRB;
+    const char* base = (DUAL && br >= 128) ? Be1 : Be0;
     int n = n0 + ((DUAL && br >= 128) ? br - 128 : br);
     n = n < N ? n : N - 1;
-    bsrc[q] = base + size_t(n) * K + piece * 8;
+    bsrc[q] = base + (size_t(n) * K) * WB + piece * 16;
   }
   const bool extra = AREM > 0 && wave < AREM;        // this wavefront loads one more A row group
   auto issue_a = [&](int ks) {
@@ -441,7 +469,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
                                        (lptr_t)(st + (NAQ * 8 + wave) * 64), 16, 0, 0);
   };
   auto issue_b = [&](int ks) {
-    const int kcol = ks * KS;
+    const int kcol = ks * KS * WB;
     uint4* st = ringB + (ks % SB) * BS;
 #pragma unroll
     for (int q = 0; q < NBQ; ++q)
@@ -485,7 +513,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   constexpr int NOPS = NBQ + NAQ;
   auto issue_op = [&](int op, uint4* stb, uint4* sta, int kcb, int kca) {
     if (op < NBQ)
-      __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[op] + kcb), (lptr_t)(stb + (op * 8 + wave) * 64),
+      __builtin_amdgcn_global_load_lds((gptr_t)(bsrc[op] + kcb * WB), (lptr_t)(stb + (op * 8 + wave) * 64),
                                        16, 0, 0);
     else if (op < NOPS)
       __builtin_amdgcn_global_load_lds((gptr_t)(asrc[op - NBQ] + kca),
@@ -538,10 +566,20 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     if constexpr (NBW > 0) {
       const uint4* Ab = ringA + (ks % SA) * AS;
       const uint4* Bb = ringB + (ks % SB) * BS;
+      float sc0 = 1.f, sc1 = 1.f;
+      if constexpr (F8) { sc0 = Se0[ks >> 1]; sc1 = Se1[ks >> 1]; }   // one block = two K steps
       auto read_frags = [&](int kk, int set) {
         const int piece = kk * 2 + (lane >> 5);
-        fb[set][0] = Bb[slot(brow0 + (lane & 31), piece)];
-        fb[set][1] = Bb[slot(brow1 + (lane & 31), piece)];
+        if constexpr (F8) {
+          // sub-step kk: eight codes at bytes kk*16 + (lane/32)*8 of the row's 64
+          const uint2 c0 = reinterpret_cast<const uint2*>(&Bb[slot_b(brow0 + (lane & 31), kk)])[lane >> 5];
+          const uint2 c1 = reinterpret_cast<const uint2*>(&Bb[slot_b(brow1 + (lane & 31), kk)])[lane >> 5];
+          fb[set][0] = widen_scaled(c0, sc0);
+          fb[set][1] = widen_scaled(c1, sc1);
+        } else {
+          fb[set][0] = Bb[slot_b(brow0 + (lane & 31), piece)];
+          fb[set][1] = Bb[slot_b(brow1 + (lane & 31), piece)];
+        }
 #pragma unroll
         for (int i = 0; i < NBW; ++i) fa[set][i] = Ab[slot(arow + i * 32 + (lane & 31), piece)];
       };
@@ -628,19 +666,20 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   }
 }
 
-template <bool DUAL, int NB>
-__device__ __forceinline__ void gemm8w_tile(const uint16_t* A, const uint16_t* Be0,
-                                            const uint16_t* Be1, uint16_t* C, int N, int K,
-                                            int row0, int row1, int n0, uint4* smem, int wave) {
-  if (wave < 4) gemm8w_body<DUAL, NB, 0>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave);
-  else gemm8w_body<DUAL, NB, 1>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave);
+template <bool DUAL, int NB, bool F8>
+__device__ __forceinline__ void gemm8w_tile(const uint16_t* A, const char* Be0, const char* Be1,
+                                            const float* Se0, const float* Se1, uint16_t* C, int N,
+                                            int K, int row0, int row1, int n0, uint4* smem,
+                                            int wave) {
+  if (wave < 4) gemm8w_body<DUAL, NB, 0, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave);
+  else gemm8w_body<DUAL, NB, 1, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave);
 }
 
-template <bool DUAL>
+template <bool DUAL, bool F8>
 __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
-    const uint16_t* __restrict__ A, const uint16_t* __restrict__ B0,
-    const uint16_t* __restrict__ B1, uint16_t* __restrict__ C, int N, int K,
-    const int32_t* __restrict__ tiles, int m_fastest) {
+    const uint16_t* __restrict__ A, const void* __restrict__ B0, const void* __restrict__ B1,
+    const float* __restrict__ S0, const float* __restrict__ S1, uint16_t* __restrict__ C, int N,
+    int K, const int32_t* __restrict__ tiles, int m_fastest) {
   constexpr int BN = DUAL ? 128 : 256;
   extern __shared__ uint4 smem[];
   const int n_ntiles = (N + BN - 1) / BN;
@@ -667,19 +706,33 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
   const int e = tiles[1 + kTileRec * mtile], row0 = tiles[2 + kTileRec * mtile],
             row1 = tiles[3 + kTileRec * mtile];
   const int n0 = ntile * BN;
-  const uint16_t* Be0 = B0 + size_t(e) * N * K;
-  const uint16_t* Be1 = DUAL ? B1 + size_t(e) * N * K : nullptr;
+  constexpr int WB = F8 ? 1 : 2;
+  const char* Be0 = static_cast<const char*>(B0) + size_t(e) * N * K * WB;
+  const char* Be1 = DUAL ? static_cast<const char*>(B1) + size_t(e) * N * K * WB : nullptr;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  switch ((row1 - row0 + 31) >> 5) {     // valid 32-row blocks of the tile
-    case 1: gemm8w_tile<DUAL, 1>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 2: gemm8w_tile<DUAL, 2>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 3: gemm8w_tile<DUAL, 3>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 4: gemm8w_tile<DUAL, 4>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 5: gemm8w_tile<DUAL, 5>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 6: gemm8w_tile<DUAL, 6>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    case 7: gemm8w_tile<DUAL, 7>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
-    default: gemm8w_tile<DUAL, 8>(A, Be0, Be1, C, N, K, row0, row1, n0, smem, wave); break;
+  // F8: the scales of the 128-row block this wavefront's weight rows lie in
+  const float* Se0 = nullptr;
+  const float* Se1 = nullptr;
+  if constexpr (F8) {
+    const int nkb = K / 128, nnb = N / 128;
+    int nb = (n0 + (wave & 3) * (DUAL ? 32 : 64)) / 128;
+    nb = nb < nnb ? nb : nnb - 1;
+    Se0 = S0 + (size_t(e) * nnb + nb) * nkb;
+    Se1 = DUAL ? S1 + (size_t(e) * nnb + nb) * nkb : Se0;
   }
+#define MOE_TILE_(NBV) \
+  gemm8w_tile<DUAL, NBV, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave)
+  switch ((row1 - row0 + 31) >> 5) {     // valid 32-row blocks of the tile
+    case 1: MOE_TILE_(1); break;
+    case 2: MOE_TILE_(2); break;
+    case 3: MOE_TILE_(3); break;
+    case 4: MOE_TILE_(4); break;
+    case 5: MOE_TILE_(5); break;
+    case 6: MOE_TILE_(6); break;
+    case 7: MOE_TILE_(7); break;
+    default: MOE_TILE_(8); break;
+  }
+#undef MOE_TILE_
 }
 
 // ----------------------------------------- MFMA GEMM, weight streaming (decode)
@@ -967,9 +1020,11 @@ void launch_skinny(const moe_config& c, int n_experts, const void* xs, const int
              (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
 }
 
+template <bool F8>
 void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const int32_t* offsets,
                     int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
-                    void* ys, const FfnWs& ws, hipStream_t s) {
+                    const float* s_gate, const float* s_up, const float* s_down, void* ys,
+                    const FfnWs& ws, hipStream_t s) {
   const int H = c.hidden, I = c.inter_local;
   // Few rows per expert means the weights are streamed about once: cap the tile
   // height at 160 rows there, which leaves room for a three-stage ring.
@@ -987,26 +1042,27 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
   constexpr int lds = 160 * 1024;         // all of a CU's LDS: the rings of the tallest tile fill it
   const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt2 * nt2 + 7) / 8 * 8;
-  auto k1 = ffn_gemm8w_kernel<true>;
-  auto k2 = ffn_gemm8w_kernel<false>;
+  auto k1 = ffn_gemm8w_kernel<true, F8>;
+  auto k2 = ffn_gemm8w_kernel<false, F8>;
   static uint64_t opted1 = 0, opted2 = 0;
   lds_opt_in(reinterpret_cast<const void*>(k1), lds, opted1);
   lds_opt_in(reinterpret_cast<const void*>(k2), lds, opted2);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
-             static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
-             static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
+             w_gate, w_up, s_gate, s_up, static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
   MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(g2), dim3(512), lds, s,
-             static_cast<const uint16_t*>(ws.hmid), static_cast<const uint16_t*>(w_down),
-             (const uint16_t*)nullptr, static_cast<uint16_t*>(ys), H, I, tiles2, 1);
+             static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr, s_down,
+             (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, tiles2, 1);
 }
 
 // Between the two: a handful of rows per expert.  GEMM-1 (K = H long) streams its
 // weights fastest through the LDS rings of the tall-tile kernel even when a tile
 // holds one or two row blocks; GEMM-2 (K = I_loc short, N = H wide) is best as
 // many small weight-streaming workgroups.  Each kernel gets its own tile table.
+template <bool F8>
 void launch_mixed(const moe_config& c, int n_experts, const void* xs, const int32_t* offsets,
                   int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
-                  void* ys, const FfnWs& ws, hipStream_t s) {
+                  const float* s_gate, const float* s_up, const float* s_down, void* ys,
+                  const FfnWs& ws, hipStream_t s) {
   const int H = c.hidden, I = c.inter_local;
   const int bm = 160, bm2 = 32;
   const int max_mt = rows_capacity / bm + n_experts;
@@ -1017,15 +1073,14 @@ void launch_mixed(const moe_config& c, int n_experts, const void* xs, const int3
   const int nt1 = (I + 127) / 128, nt2 = (H + 63) / 64;
   constexpr int lds = 160 * 1024;
   const int g1 = (max_mt * nt1 + 7) / 8 * 8;
-  auto k1 = ffn_gemm8w_kernel<true>;
+  auto k1 = ffn_gemm8w_kernel<true, F8>;
   static uint64_t opted1 = 0;
   lds_opt_in(reinterpret_cast<const void*>(k1), lds, opted1);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
-             static_cast<const uint16_t*>(w_gate), static_cast<const uint16_t*>(w_up),
-             static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
-  MOE_LAUNCH(MOE_K_FFN_GEMM2, (ffn_skinny_kernel<false, false>), dim3(size_t(max_mt2) * nt2), dim3(256),
-             0, s, static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr,
-             (const float*)nullptr, (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles2);
+             w_gate, w_up, s_gate, s_up, static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
+  MOE_LAUNCH(MOE_K_FFN_GEMM2, (ffn_skinny_kernel<false, F8>), dim3(size_t(max_mt2) * nt2), dim3(256),
+             0, s, static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr, s_down,
+             (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles2);
 }
 
 }  // namespace
@@ -1056,7 +1111,11 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
   const int avg = rows_capacity / n_experts;
   const bool fp8 = c.weight_dtype == MOE_FP8_E4M3_B128;
 #define MOE_FFN_ARGS c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, s_gate, s_up, s_down, ys, ws, s
-  if (fp8 && H % 128 == 0 && I % 128 == 0) {
+  if (fp8 && H % 128 == 0 && I % 128 == 0 && avg > 12) {
+    // e4m3 weight tiles in the LDS rings of the tall-tile kernel (the scaled weight
+    // is rounded to bf16 there; below, the scale multiplies fp32 partial sums)
+    launch_mfma256<true>(MOE_FFN_ARGS);
+  } else if (fp8 && H % 128 == 0 && I % 128 == 0) {
     launch_skinny<true>(MOE_FFN_ARGS);
   } else if (fp8) {
     launch_mfma_pair<32, 128, 32, 32, 256, 64, true>(MOE_FFN_ARGS);
@@ -1065,8 +1124,8 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
     // per expert the weight-streaming kernel wins both GEMMs, from about twelve on
     // the tall-tile kernel does, in between each takes the GEMM it is better at
     if (avg <= 2) launch_skinny<false>(MOE_FFN_ARGS);
-    else if (avg <= 12) launch_mixed(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
-    else launch_mfma256(c, n_experts, xs, offsets, rows_capacity, w_gate, w_up, w_down, ys, ws, s);
+    else if (avg <= 12) launch_mixed<false>(MOE_FFN_ARGS);
+    else launch_mfma256<false>(MOE_FFN_ARGS);
   } else if (avg <= 32) {
     launch_mfma_pair<32, 128, 32, 32, 256, 64, false>(MOE_FFN_ARGS);
   } else if (avg <= 64) {
