@@ -2,7 +2,7 @@
 """Benchmark of one GPU's MoE-layer share: route -> dispatch -> expert FFN ->
 combine on seeded synthetic layers, one JSON line on stdout.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2p|c2d|c2x|c3|c3d|c4|c4q|c5|c1]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2p|c2d|c2x|c3|c3d|c4|c4w|c4q|c5|c1]
 
 A step is one pass of the whole path over one batch, inputs resident in HBM.
 `value` is tokens/s of the share; `roofline` prices the dominant kernel against
@@ -31,6 +31,7 @@ DESCR = {
     "c2x": "Qwen3-30B-A3B-shaped full layer, the largest prefill step (16 x 4096 tokens): hidden 2048, 128 experts top-8, I 768, bf16",
     "c3d": "Qwen3-235B-A22B-shaped EP=8 share, decode 256 tokens: hidden 4096, 16 of 128 experts, I 1536, bf16",
     "c4": "DeepSeek-R1-shaped TP=2 x EP share: 16384 tokens, hidden 7168, 32 of 256 experts + shared, I 1024, bf16",
+    "c4w": "the c4 share with e4m3 block-128 weights and bf16 activations (weight tiles widened to bf16 in the tall-tile kernel)",
     "c4q": "the c4 share with e4m3 block-128 weights and expert-FFN activations quantised 1x128 to e4m3 (fp8 MFMA)",
     "c5": "DeepSeek-R1-shaped decode stress: 256 tokens, fp8-e4m3 block-128 weights, forced Zipf routing",
 }

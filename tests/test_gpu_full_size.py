@@ -12,7 +12,7 @@ from helpers import (TOL, check_dispatch, check_routing, dev, host, inputs, make
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["c2d", "c2p", "c3d", "c3", "c5", "c4", "c4q", "c2x"])
+@pytest.mark.parametrize("name", ["c2d", "c2p", "c3d", "c3", "c5", "c4", "c4w", "c4q", "c2x"])
 def test_full_size_workload(name):
     w = gen.CONFIGS[name]
     print("workload", name, "generating inputs", flush=True)

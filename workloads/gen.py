@@ -100,6 +100,11 @@ CONFIGS: Dict[str, Workload] = {
                    score_fn="sigmoid", routed_scale=2.5, n_groups=8, topk_groups=4,
                    group_score_n=2, expert_lo=0, expert_hi=32, tp=2, tp_rank=0,
                    shared_expert=True, select_bias_std=0.05),
+    # the C4 share with e4m3 block-scaled weights (bf16 activations)
+    "c4w": Workload("c4w", 1004, T=16384, H=7168, E=256, k=8, I=2048,
+                    score_fn="sigmoid", routed_scale=2.5, n_groups=8, topk_groups=4,
+                    group_score_n=2, expert_lo=0, expert_hi=32, tp=2, tp_rank=0,
+                    shared_expert=True, select_bias_std=0.05, weight_dtype="fp8"),
     # the C4 share with e4m3 weights and 8-bit activations in the expert FFN
     "c4q": Workload("c4q", 1004, T=16384, H=7168, E=256, k=8, I=2048,
                     score_fn="sigmoid", routed_scale=2.5, n_groups=8, topk_groups=4,
