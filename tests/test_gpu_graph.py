@@ -22,6 +22,12 @@ CASES = {
     # shared expert on its second stream inside the capture, sigmoid grouped routing
     "shared": gen.CONFIGS["c4"].replace(name="graph_shared", T=300, H=512, E=64, k=8, I=256,
                                         expert_lo=0, expert_hi=16),
+    # e4m3 weights with enough rows per expert for the tall-tile kernel's fp8 weight tiles
+    "fp8_weights": gen.CONFIGS["c5"].replace(name="graph_fp8", T=300, H=512, E=64, k=8, I=256,
+                                             expert_lo=0, expert_hi=16, zipf_s=None),
+    # long gate rows at a few tokens: the exact route as two kernels
+    "long_gate_rows": gen.CONFIGS["c3"].replace(name="graph_long_rows", T=9, H=8192, E=128, k=8, I=64,
+                                                expert_lo=0, expert_hi=16),
 }
 
 
