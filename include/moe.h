@@ -58,12 +58,12 @@ typedef enum { MOE_SCORE_SOFTMAX = 0, MOE_SCORE_SIGMOID = 1 } moe_score_fn;
  */
 typedef struct {
   int32_t hidden;        /* H, multiple of 8                                              */
-  int32_t n_experts;     /* E, global routed experts                                      */
+  int32_t n_experts;     /* E, global routed experts, E <= 512                            */
   int32_t top_k;         /* k, 1 <= k <= 32, k <= E                                       */
   int32_t score_fn;      /* moe_score_fn                                                  */
   int32_t renormalize;   /* 1: weights of the k picked experts sum to routed_scale        */
   float routed_scale;    /* multiplies the weights (1.0, or 2.5 for the DeepSeek shape)   */
-  int32_t n_groups;      /* G; 1 = no group limit; E % G == 0                             */
+  int32_t n_groups;      /* G; 1 = no group limit; E % G == 0; G <= 64                    */
   int32_t topk_groups;   /* groups kept, 1 <= topk_groups <= G                            */
   int32_t group_score_n; /* group score = sum of this many largest keys of the group     */
   int32_t expert_lo;     /* this GPU hosts global experts [expert_lo, expert_hi)          */
@@ -102,6 +102,7 @@ const char* moe_status_string(moe_status s);
  *   logits_in  [T,E] fp32 or NULL: when given the dot products are skipped and
  *              these are the logits (x and gate_w may then be NULL)
  *   topk_ids   out [T,k] int32 global expert ids     topk_w out [T,k] fp32
+ * T * E must stay below 2^31 (MOE_ERR_UNSUPPORTED otherwise).
  */
 moe_status moe_route(const moe_config* cfg, int32_t T, const void* x, const void* gate_w,
                      const float* logit_bias, const float* select_bias,
@@ -120,6 +121,7 @@ moe_status moe_route(const moe_config* cfg, int32_t T, const void* x, const void
  *   inv     out [T*k]       a -> position, or -1 when the expert is not local
  *   xs      out [T*k, H]    act dtype; first A_loc rows valid: xs[pos] = x[perm[pos]/k]
  * counts/offsets stay on the device; later calls read them there.
+ * T * k must not exceed 2^30 (MOE_ERR_UNSUPPORTED otherwise).
  */
 moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
                         const int32_t* topk_ids, int32_t* counts, int32_t* offsets,
