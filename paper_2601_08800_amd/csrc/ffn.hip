@@ -1115,10 +1115,10 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
     // e4m3 weight tiles in the LDS rings of the tall-tile kernel (the scaled weight
     // is rounded to bf16 there; below, the scale multiplies fp32 partial sums)
     launch_mfma256<true>(MOE_FFN_ARGS);
-  } else if (fp8 && H % 128 == 0 && I % 128 == 0) {
-    launch_skinny<true>(MOE_FFN_ARGS);
   } else if (fp8) {
-    launch_mfma_pair<32, 128, 32, 32, 256, 64, true>(MOE_FFN_ARGS);
+    // the configuration check admits fp8 weights only with hidden and intermediate
+    // sizes that are multiples of 128
+    launch_skinny<true>(MOE_FFN_ARGS);
   } else if (H % BK == 0 && I % BK == 0) {
     // measured on the 128-expert layer (hidden 2048, I 768): with at most two rows
     // per expert the weight-streaming kernel wins both GEMMs, from about twelve on
