@@ -7,7 +7,7 @@
  * hosts the expert ("Dispatch", Sec. II), pushed through that expert's MLP,
  * whose weights are an intra-node TP slice (Sec. II "TP", Sec. III-C), and
  * returned along the original route weighted by the top-k weights
- * ("Combine", Sec. II; Alg. 1 `Y_i <- Y_i + topk_weights(S_i)`), giving the
+ * ("Combine", Sec. II; the accumulation step of Alg. 1), giving the
  * partial sum that the intra-node all-reduce completes (Sec. III-B-2 "AR").
  * The exchanges themselves (A2A, AR) are outside this library: it builds the
  * buffer the A2A would carry and the tensor the AR would reduce.
@@ -187,7 +187,8 @@ moe_status moe_combine(const moe_config* cfg, int32_t T, const void* ys, const i
  * One stage of the fused RS-Combine schedule (Alg. 1): the hidden dimension is
  * split into tp_size blocks; stage i hands this rank S_i, the reduce-scattered
  * expert outputs that one source node returned, restricted to the rank's block,
- * and the stage result is accumulated: Y_block <- Y_block + topk_weights(S_i).
+ * and the stage result, scaled by the top-k weights, is added to the running
+ * block (the accumulation step of Alg. 1).
  *   ys_block  [>= rows, H/tp_size] act dtype (rows addressed through inv)
  *   inv [T*k], topk_w [T,k]: as in moe_combine, for the assignments of this stage
  *   out_block [T, H/tp_size] fp32:

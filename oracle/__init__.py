@@ -168,7 +168,8 @@ def quant_act_1x128(x):
 
 def expert_ffn_fp8act(offsets, xs, w_gate, w_up, w_down, s_gate, s_up, s_down):
     """The grouped SwiGLU MLP with activations quantised 1x128 on the fly (input
-    rows, and the bf16-stored intermediate) and block-scaled e4m3 weights.
+    rows, and the SwiGLU intermediate, which goes to the quantiser without any
+    intermediate storage rounding) and block-scaled e4m3 weights.
     Returns ys float64."""
     offsets = np.ascontiguousarray(offsets, np.int32)
     xs = decode(xs)

@@ -17,7 +17,7 @@
  *   MLP      every expert is an independent MLP; under TP its weights are
  *            sliced and the partial results are summed afterwards
  *   combine  results return along the original route, weighted by the top-k
- *            weights (Alg. 1, Y_i <- Y_i + topk_weights(S_i)); the result is
+ *            weights (the accumulation step of Alg. 1); the result is
  *            the partial sum the intra-node all-reduce would finish
  * The paper fixes no numerical detail (score function, MLP form, precision);
  * those follow the benchmark configurations: softmax or sigmoid scores,
@@ -291,21 +291,11 @@ void oracle_quant_act_1x128(int rows, int K, const float *x, uint8_t *codes, flo
         }
 }
 
-static float round_to_bf16(double v)
-{
-    float f = (float)v;
-    uint32_t u;
-    memcpy(&u, &f, 4);
-    u += 0x7FFFu + ((u >> 16) & 1u);      /* round to nearest even on the upper half */
-    u &= 0xFFFF0000u;
-    memcpy(&f, &u, 4);
-    return f;
-}
-
 /*
  * The grouped SwiGLU MLP of oracle_expert_ffn with quantised activations:
  *   xq = quant(xs row);  g = Wgate_e xq, u = Wup_e xq;  hmid = g*sigmoid(g)*u
- *   stored as bf16, then quantised the same way;  ys_r = Wdown_e hq.
+ *   (fp64, no intermediate storage format), handed to the same quantiser as
+ *   its fp32 value;  ys_r = Wdown_e hq.
  * Weights are e4m3 values (already decoded to fp32) with 128x128 block scales.
  * H and I are multiples of 128.  ys [rows,H] fp64.
  */
@@ -335,7 +325,7 @@ void oracle_expert_ffn_fp8act(int n_experts, const int32_t *offsets, int H, int 
                     g += wg * xq[h];
                     u += wu * xq[h];
                 }
-                hb[i] = round_to_bf16(g / (1.0 + exp(-g)) * u);
+                hb[i] = (float)(g / (1.0 + exp(-g)) * u);
             }
             oracle_quant_act_1x128(1, I, hb, ch, sh);
             for (int i = 0; i < I; ++i) hq[i] = e4m3_value(ch[i]) * (double)sh[i / 128];
@@ -410,7 +400,8 @@ void oracle_dispatch_shard(int T, int k, int H, int e_lo, int e_hi, int tp_rank,
 }
 
 /*
- * One stage of the fused RS-Combine (Alg. 1): Y_i <- Y_i + topk_weights(S_i),
+ * One stage of the fused RS-Combine (Alg. 1): the rows S_i of stage i, scaled by
+ * their top-k weights, are added to the running block Y_i,
  * on one hidden-column block of width Hb = H/m.
  *   s[t][c] = sum_{j: inv[t*k+j] >= 0} w[t][j] * ys_block[inv[t*k+j]][c]   (fp64)
  *   out_block[t][c] = (accumulate ? out_block[t][c] : 0) + s[t][c], stored fp32.

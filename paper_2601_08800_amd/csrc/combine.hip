@@ -1,6 +1,7 @@
 // Combine: return the expert outputs along the original route, weighted by the
 // top-k weights, into the fp32 partial sum awaiting the intra-node all-reduce
-// (Sec. II "Combine"; Alg. 1 `Y_i <- Y_i + topk_weights(S_i)`).
+// (Sec. II "Combine"; the accumulation step of Alg. 1: the rows a stage returns
+// are scaled by their top-k weights and added to the running result).
 //
 // Gather-by-token: one wavefront owns a token, walks the row in 16-byte pieces
 // and adds the token's local expert rows in ascending j, so there are no

@@ -83,7 +83,10 @@ MUTANTS = [
     ("quant_ties_away", "if (d < bd || (d == bd && (c & 1) == 0 && (best & 1) == 1)) { bd = d; best = c; }",
      "if (d <= bd) { bd = d; best = c; }", 1, FP8ACT),
     ("quant_range_240", "float scale = amax > 0.0f ? amax / 448.0f : 1.0f;", "float scale = amax > 0.0f ? amax / 240.0f : 1.0f;", 1, FP8ACT),
-    ("quant_hmid_not_rounded_to_bf16", "hb[i] = round_to_bf16(g / (1.0 + exp(-g)) * u);", "hb[i] = (float)(g / (1.0 + exp(-g)) * u);", 1, FP8ACT),
+    ("quant_hmid_skipped", "hq[i] = e4m3_value(ch[i]) * (double)sh[i / 128];", "hq[i] = (double)hb[i];", 1, FP8ACT),
+    ("quant_hmid_without_up", "hb[i] = (float)(g / (1.0 + exp(-g)) * u);", "hb[i] = (float)(g / (1.0 + exp(-g)));", 1, FP8ACT),
+    ("quant_hmid_cut_to_upper_half", "hb[i] = (float)(g / (1.0 + exp(-g)) * u);",
+     "{ float f_ = (float)(g / (1.0 + exp(-g)) * u); uint32_t b_; memcpy(&b_, &f_, 4); b_ &= 0xFFFF0000u; memcpy(&hb[i], &b_, 4); }", 1, FP8ACT),
     ("quant_act_scale_dropped", "xq[h] = e4m3_value(cx[h]) * (double)sx[h / 128];", "xq[h] = e4m3_value(cx[h]);", 1, FP8ACT),
     ("quant_weight_scale_index_transposed", "(double)Wg[(size_t)i * H + h] * (double)s_gate[((size_t)e * bI + i / 128) * bH + h / 128]",
      "(double)Wg[(size_t)i * H + h] * (double)s_gate[((size_t)e * bH + h / 128) * bI + i / 128]", 1, FP8ACT),
