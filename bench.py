@@ -2,7 +2,11 @@
 """Benchmark of one GPU's MoE-layer share: route -> dispatch -> expert FFN ->
 combine on seeded synthetic layers, one JSON line on stdout.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2p|c2d|c2x|c3|c3d|c4|c4w|c4q|c5|c1]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c2p|c2d|c2x|c3|c3d|c4w|c4q|c5|c1]
+
+The default workload is c4 (the largest single-GPU configuration: the DeepSeek-R1-
+shaped TP=2 x EP share at 16 384 prefill tokens); with it the line also carries a
+`per_workload` table (c2p, c3, c5, c2d: shorter measurements of the same kind).
 
 A step is one pass of the whole path over one batch, inputs resident in HBM.
 `value` is tokens/s of the share; `roofline` prices the dominant kernel against
@@ -58,48 +62,29 @@ def algorithmic_work(w, a_loc, e_touched, tokens_local):
     return work
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2p", choices=list(DESCR))
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--no-extras", action="store_true",
-                    help="skip the HIP-graph replay and the next_rows measurements (profiling runs)")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs one GPU's share on one GPU; --gpus %d is not supported "
-              "(no collectives, no sharding across GPUs)" % args.gpus, file=sys.stderr)
-        return 2
-
+def measure(moe, name, steps, warmup, args, full):
+    """One workload: build the layer, time `steps` whole steps between two device
+    synchronisations, and return the fields of the benchmark line.  `full`: also
+    the HIP-graph replay, the collective-ready layouts and the CPU baseline."""
     import numpy as np
     import torch
     from workloads import gen
-    import paper_2601_08800_amd as moe
     from paper_2601_08800_amd.layer import config_from_workload, to_device
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU", file=sys.stderr)
-        return 2
-    moe.load_library()                      # fails loudly when the HIP library is not built
-    w = gen.CONFIGS[args.workload]
+    w = gen.CONFIGS[name]
     t0 = time.time()
     x_np, gate = gen.make_x(w), gen.make_gate(w)
     experts = gen.make_local_experts(w)
     shared = gen.make_shared_expert(w) if w.shared_expert else None
     forced_np = gen.make_forced_routing(w) if w.zipf_s is not None else None
-    print("inputs generated in %.1f s" % (time.time() - t0), file=sys.stderr, flush=True)
+    print("%s: inputs generated in %.1f s" % (name, time.time() - t0), file=sys.stderr, flush=True)
 
     L = moe.MoELayerShare(config_from_workload(w), w.T, gate, experts, shared,
                           fp8_activations=w.fp8_activations)
     x = to_device(x_np)
     forced = None if forced_np is None else (to_device(forced_np[0]), to_device(forced_np[1]))
 
-    if args.calibration_copy:
+    if args.calibration_copy and full:
         # a copy of known size: rocprofv3 FETCH_SIZE / WRITE_SIZE of this dispatch
         # give the factor that turns the counters into bytes
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -107,7 +92,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         L.forward(x, forced)
     torch.cuda.synchronize()
     # untimed pass with an event pair around every kernel: the per-stage table,
@@ -116,8 +101,8 @@ def main():
     # stream so that each kernel's duration is its own.
     overlap = L.overlap_shared
     L.overlap_shared = False
-    moe.moe_profile_enable(64 * max(args.steps, 1))
-    for _ in range(args.steps):
+    moe.moe_profile_enable(64 * max(steps, 1))
+    for _ in range(steps):
         L.forward(x, forced)
     torch.cuda.synchronize()
     prof = moe.moe_profile_read()
@@ -132,15 +117,29 @@ def main():
     torch.cuda.synchronize()
     moe.moe_profile_read()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         L.forward(x, forced)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof_timed = moe.moe_profile_read()
     moe.moe_profile_filter(None)
     moe.moe_profile_enable(0)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
     value = w.T / (ms_per_step * 1e-3)
+
+    # spread of single steps: at least 30 steps, each between two events on the
+    # stream the step starts and ends on (the side stream joins before combine)
+    n_single = max(30, steps)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(n_single)]
+    for a, b in evs:
+        a.record()
+        L.forward(x, forced)
+        b.record()
+    torch.cuda.synchronize()
+    single = sorted(a.elapsed_time(b) for a, b in evs)
+    step_stats = {"n": n_single, "median_ms": round(single[n_single // 2], 4), "min_ms": round(single[0], 4),
+                  "max_ms": round(single[-1], 4)}
 
     counts = L.counts.cpu().numpy()
     inv = L.inv.cpu().numpy().reshape(w.T, w.k)
@@ -155,20 +154,21 @@ def main():
     work = algorithmic_work(w, a_loc, e_touched, tokens_local)
 
     stages = {}
-    for name, (ms, n) in prof.items():
-        us = ms * 1e3 / args.steps
-        st = {"us_per_step": round(us, 2), "launches_per_step": n / args.steps}
-        if name in work and us > 0:
-            fl, by = work[name]
+    for kname, (ms, n) in prof.items():
+        us = ms * 1e3 / steps
+        st = {"us_per_step": round(us, 2), "launches_per_step": n / steps}
+        if kname in work and us > 0:
+            fl, by = work[kname]
             st["GBps"] = round(by / (us * 1e-6) / 1e9, 1)
             if fl:
                 st["TFLOPs"] = round(fl / (us * 1e-6) / 1e12, 1)
-        stages[name] = st
+        stages[kname] = st
 
     fl, by = work[dom]
     # measured inside the timed region; with the shared expert on a second stream
     # the kernels of the two streams share the CUs, so the one-stream pass is used
-    dur = (prof[dom][0] if overlap else prof_timed[dom][0]) * 1e-3 / args.steps
+    dur = (prof[dom][0] if overlap else prof_timed[dom][0]) * 1e-3 / steps
+    n_launch = (prof[dom][1] if overlap else prof_timed[dom][1]) / steps
     peak_tf = 5000.0 if w.fp8_activations else PEAK_MFMA_TFLOPS[w.weight_dtype]   # fp8 x fp8 MFMA
     t_mfma = fl / (peak_tf * 1e12)
     t_hbm = by / (PEAK_HBM_GBS * 1e9)
@@ -182,19 +182,22 @@ def main():
     roof["traffic"] = None
     roof["kernel"] = dom
     roof["kernel_us"] = round(dur * 1e6, 2)
+    roof["launches_per_step"] = n_launch
+    roof["duration_from"] = "one-stream pass (the timed step overlaps the shared expert on a second stream)" \
+        if overlap else "timed region"
     roof["algorithmic_flops"] = fl
     roof["algorithmic_bytes"] = by
     roof["other_bound_frac"] = round((t_hbm if t_mfma >= t_hbm else t_mfma) / dur, 4)
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            roof["traffic"] = json.load(open(tpath)).get(args.workload, {}).get(dom)
+            roof["traffic"] = json.load(open(tpath)).get(name, {}).get(dom)
         except Exception:
             pass
 
     out = {
         "metric": "moe_layer_share_tokens_per_s", "value": round(value, 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "fp8" if w.fp8_activations else {"f32": "f32", "bf16": "bf16", "fp8": "bf16"}[w.weight_dtype],
         "data": "synthetic",
@@ -203,40 +206,80 @@ def main():
                    "inter_local": w.I_loc, "local_assignments": a_loc,
                    "tokens_rescored_fp64": n_rescored, "shared_expert_on_second_stream": bool(overlap),
                    "weight_dtype": w.weight_dtype},
+        "single_steps": step_stats,
         "roofline": roof,
         "stages": stages,
     }
+    if not full:
+        return out
 
-    if args.no_extras:
-        if not args.no_cpu_baseline:
-            out["cpu_baseline"] = cpu_baseline(w, x_np, gate, experts, shared, forced_np,
-                                               args.cpu_seconds)
-        print(json.dumps(out), flush=True)
-        return 0
-
-    # the same step replayed from a HIP graph (launch overhead off the critical path)
-    try:
-        graph = L.capture(x, forced)
-        for _ in range(3):
-            graph.replay()
-        torch.cuda.synchronize()
-        g0 = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        g_ms = (time.perf_counter() - g0) * 1e3 / args.steps
-        out["hip_graph_replay"] = {"ms_per_step": round(g_ms, 4), "tokens_per_s": round(w.T / (g_ms * 1e-3), 1)}
-        del graph
-    except Exception as exc:            # reported, never fatal for the benchmark line
-        out["hip_graph_replay"] = {"error": str(exc)[:200]}
-
-    out["next_rows"] = next_rows(moe, L, w, x, a_loc, tokens_local, max(args.steps, 5))
-    if forced is not None:
-        out["route_separately"] = route_separately(moe, L, x, max(args.steps, 5))
-
+    if not args.no_extras:
+        # the same step replayed from a HIP graph (launch overhead off the critical path)
+        try:
+            graph = L.capture(x, forced)
+            for _ in range(3):
+                graph.replay()
+            torch.cuda.synchronize()
+            g0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            g_ms = (time.perf_counter() - g0) * 1e3 / steps
+            out["hip_graph_replay"] = {"ms_per_step": round(g_ms, 4), "tokens_per_s": round(w.T / (g_ms * 1e-3), 1)}
+            del graph
+        except Exception as exc:            # reported, never fatal for the benchmark line
+            out["hip_graph_replay"] = {"error": str(exc)[:200]}
+        out["next_rows"] = next_rows(moe, L, w, x, a_loc, tokens_local, max(steps, 5))
+        if forced is not None:
+            out["route_separately"] = route_separately(moe, L, x, max(steps, 5))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x_np, gate, experts, shared, forced_np,
                                            args.cpu_seconds)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4", choices=list(DESCR))
+    ap.add_argument("--also", default=None,
+                    help="comma-separated workloads for the per_workload table "
+                         "(default: c2p,c3,c5,c2d with the default workload, none otherwise)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the HIP-graph replay, the next_rows measurements and the per_workload table (profiling runs)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one GPU's share on one GPU; --gpus %d is not supported "
+              "(no collectives, no sharding across GPUs)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2601_08800_amd as moe
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 2
+    moe.load_library()                      # fails loudly when the HIP library is not built
+    out = measure(moe, args.workload, args.steps, args.warmup, args, True)
+    also = args.also
+    if also is None:
+        also = "c2p,c3,c5,c2d" if (args.workload == "c4" and not args.no_extras) else ""
+    table = {}
+    for name in [n for n in also.split(",") if n]:
+        torch.cuda.empty_cache()
+        r = measure(moe, name, args.steps, min(args.warmup, 3), args, False)
+        table[name] = {"tokens_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+                       "single_steps": r["single_steps"], "roofline": r["roofline"],
+                       "tokens_rescored_fp64": r["config"]["tokens_rescored_fp64"],
+                       "stage_us": {k: v["us_per_step"] for k, v in r["stages"].items()}}
+    if table:
+        out["per_workload"] = table
     print(json.dumps(out), flush=True)
     return 0
 

@@ -6,7 +6,7 @@
 //              them per local expert with ballots (one per bit of the expert
 //              index, no atomics) and notes every
 //              assignment's rank among its expert's assignments of the sub-chunk
-//   2. scan    per expert (one wavefront each) an exclusive scan over the
+//   2. scan    per expert (a workgroup of four wavefronts each) an exclusive scan over the
 //              sub-chunks -> counts; offsets = exclusive scan over experts,
 //              rebuilt in LDS by every scatter workgroup
 //   3. place   position = offsets[e] + start of the sub-chunk's run + rank

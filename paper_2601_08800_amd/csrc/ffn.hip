@@ -17,9 +17,10 @@
 // per workgroup, operands global -> LDS directly, LDS rings), ffn_skinny_kernel
 // (decode and fp8 weights: weight streaming, K split across wavefronts, no LDS
 // staging) and the register-staged ffn_gemm_kernel for the shapes in between.
-// fp8 weights: e4m3 codes are widened to bf16 (exact) in registers or on the
-// way into LDS; the 128x128 block scale multiplies the fp32 partial sum of each
-// 128-deep K block.
+// fp8 weights: the weight-streaming kernel widens the e4m3 codes to bf16 in
+// registers (exact) and multiplies the fp32 partial sum of each 128-deep K block
+// by the 128x128 block scale; the tall-tile kernel keeps the codes in its LDS
+// ring and rounds code * scale to bf16 on the way to the matrix unit.
 #include <type_traits>
 
 #include "moe_internal.h"
@@ -134,18 +135,19 @@ __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restric
 // ------------------------------------------------------------ MFMA GEMM
 // C[rows, N] = A[rows, K] * B_e[N, K]^T over the M tiles of the table.
 // DUAL: B0 = gate, B1 = up, C = silu(A B0^T) .* (A B1^T).
-template <int BM, int BN, int WM, int WN, bool DUAL, bool FP8>
+// Register-staged variant for bf16 shapes whose K is not a multiple of 64 (it
+// zero-fills the K tail).
+template <int BM, int BN, int WM, int WN, bool DUAL>
 __global__ __launch_bounds__(256) void ffn_gemm_kernel(
     const uint16_t* __restrict__ A, const void* __restrict__ B0, const void* __restrict__ B1,
-    const float* __restrict__ S0, const float* __restrict__ S1, uint16_t* __restrict__ C, int N,
-    int K, const int32_t* __restrict__ tiles) {
+    uint16_t* __restrict__ C, int N, int K, const int32_t* __restrict__ tiles) {
   constexpr int BROWS = DUAL ? 2 * BN : BN;
   constexpr int WGN = BN / WN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int NACC = DUAL ? 2 : 1;
   static_assert((BM / WM) * WGN == 4, "four wavefronts");
   constexpr int A_PER = BM * 8 / 256;
-  constexpr int B_PER = FP8 ? BROWS * 4 / 256 : BROWS * 8 / 256;
+  constexpr int B_PER = BROWS * 8 / 256;
 
   // dynamic LDS: A double buffer, then B double buffer
   extern __shared__ uint4 smem[];
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int ksteps = (K + BK - 1) / BK;
-  const size_t wbytes = FP8 ? 1 : 2;
+  const size_t wbytes = 2;
   const char* Be0 = static_cast<const char*>(B0) + size_t(e) * N * K * wbytes;
   const char* Be1 = DUAL ? static_cast<const char*>(B1) + size_t(e) * N * K * wbytes : nullptr;
 
@@ -179,19 +181,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
                          : make_uint4(0, 0, 0, 0);
       }
     }
-    if (FP8) {
-      const int lrow = tid >> 2, piece = tid & 3;    // 16 codes per piece
-      const int kcol = ks * BK + piece * 16;
-#pragma unroll
-      for (int i = 0; i < B_PER; ++i) {
-        const int lr = lrow + 64 * i;
-        const char* base = (DUAL && lr >= BN) ? Be1 : Be0;
-        int n = n0 + ((DUAL && lr >= BN) ? lr - BN : lr);
-        n = n < N ? n : N - 1;
-        rb[i] = kcol < K ? *reinterpret_cast<const uint4*>(base + size_t(n) * K + kcol)
-                         : make_uint4(0, 0, 0, 0);
-      }
-    } else {
+    {
       const int lrow = tid >> 3, piece = tid & 7;
       const int kcol = ks * BK + piece * 8;
 #pragma unroll
@@ -211,25 +201,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
 #pragma unroll
       for (int i = 0; i < A_PER; ++i) As[buf][swz(lrow + 32 * i, piece)] = ra[i];
     }
-    if (FP8) {
-      const int lrow = tid >> 2, piece = tid & 3;
-#pragma unroll
-      for (int i = 0; i < B_PER; ++i) {
-        const uint32_t src[4] = {rb[i].x, rb[i].y, rb[i].z, rb[i].w};
-        uint32_t o[8];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          // four e4m3 codes -> four fp32 -> upper halves (exact: 3 mantissa bits)
-          const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(src[q], false);
-          const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(src[q], true);
-          o[2 * q] = (__float_as_uint(lo[0]) >> 16) | (__float_as_uint(lo[1]) & 0xffff0000u);
-          o[2 * q + 1] = (__float_as_uint(hi[0]) >> 16) | (__float_as_uint(hi[1]) & 0xffff0000u);
-        }
-        const int r = lrow + 64 * i;
-        Bs[buf][swz(r, 2 * piece)] = make_uint4(o[0], o[1], o[2], o[3]);
-        Bs[buf][swz(r, 2 * piece + 1)] = make_uint4(o[4], o[5], o[6], o[7]);
-      }
-    } else {
+    {
       const int lrow = tid >> 3, piece = tid & 7;
 #pragma unroll
       for (int i = 0; i < B_PER; ++i) Bs[buf][swz(lrow + 32 * i, piece)] = rb[i];
@@ -237,7 +209,6 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
   };
 
   f32x16 acc[NACC][TM][TN];
-  f32x16 part[FP8 ? NACC : 1][FP8 ? TM : 1][FP8 ? TN : 1];   // fp8: sum of the current K block
 #pragma unroll
   for (int a = 0; a < NACC; ++a)
 #pragma unroll
@@ -245,10 +216,7 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          acc[a][i][j][q] = 0.f;
-          if constexpr (FP8) part[a][i][j][q] = 0.f;
-        }
+        for (int q = 0; q < 16; ++q) acc[a][i][j][q] = 0.f;
 
   gload(0);
   lstore(0);
@@ -270,32 +238,8 @@ __global__ __launch_bounds__(256) void ffn_gemm_kernel(
           const bf16x8 bf = __builtin_bit_cast(
               bf16x8, Bs[buf][swz(a * BN + wn * WN + j * 32 + (lane & 31), piece)]);
 #pragma unroll
-          for (int i = 0; i < TM; ++i) {
-            if constexpr (FP8)
-              part[a][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, part[a][i][j], 0, 0, 0);
-            else
-              acc[a][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[a][i][j], 0, 0, 0);
-          }
-        }
-    }
-    if constexpr (FP8) if ((ks & 1) == 1 || ks + 1 == ksteps) {
-      // end of a 128-deep K block: fold the block's partial sum in, scaled
-      const int kb = ks >> 1, nkb = (K + 127) / 128, nnb = (N + 127) / 128;
-#pragma unroll
-      for (int a = 0; a < NACC; ++a)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          int n = n0 + wn * WN + j * 32;
-          n = n < N ? n : N - 1;
-          const float* S = a == 0 ? S0 : S1;
-          const float sc = S[(size_t(e) * nnb + n / 128) * nkb + kb];
-#pragma unroll
           for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-              acc[a][i][j][q] = fmaf(sc, part[a][i][j][q], acc[a][i][j][q]);
-              part[a][i][j][q] = 0.f;
-            }
+            acc[a][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[a][i][j], 0, 0, 0);
         }
     }
     if (ks + 1 < ksteps) lstore(buf ^ 1);
@@ -976,7 +920,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float* __restrict__ 
     }
 }
 
-template <int BM, int BN1, int WM, int WN1, int BN2, int WN2, bool FP8>
+template <int BM, int BN1, int WM, int WN1, int BN2, int WN2>
 void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const int32_t* offsets,
                       int rows_capacity, const void* w_gate, const void* w_up, const void* w_down,
                       const float* s_gate, const float* s_up, const float* s_down, void* ys,
@@ -987,18 +931,18 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
                      rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0, 0,
              (int32_t*)nullptr);
   const int nt1 = (I + BN1 - 1) / BN1, nt2 = (H + BN2 - 1) / BN2;
-  auto k1 = ffn_gemm_kernel<BM, BN1, WM, WN1, true, FP8>;
-  auto k2 = ffn_gemm_kernel<BM, BN2, WM, WN2, false, FP8>;
+  auto k1 = ffn_gemm_kernel<BM, BN1, WM, WN1, true>;
+  auto k2 = ffn_gemm_kernel<BM, BN2, WM, WN2, false>;
   constexpr int lds1 = 2 * (BM + 2 * BN1) * 8 * 16, lds2 = 2 * (BM + BN2) * 8 * 16;
   static uint64_t opted1 = 0, opted2 = 0;
   lds_opt_in(reinterpret_cast<const void*>(k1), lds1, opted1);
   lds_opt_in(reinterpret_cast<const void*>(k2), lds2, opted2);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(size_t(max_mt) * nt1), dim3(256), lds1, s,
-                     static_cast<const uint16_t*>(xs), w_gate, w_up, s_gate, s_up,
+                     static_cast<const uint16_t*>(xs), w_gate, w_up,
                      static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles);
   MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(size_t(max_mt) * nt2), dim3(256), lds2, s,
-                     static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr, s_down,
-                     (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles);
+                     static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr,
+                     static_cast<uint16_t*>(ys), H, I, ws.tiles);
 }
 
 template <bool FP8>
@@ -1127,11 +1071,11 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
     else if (avg <= 12) launch_mixed<false>(MOE_FFN_ARGS);
     else launch_mfma256<false>(MOE_FFN_ARGS);
   } else if (avg <= 32) {
-    launch_mfma_pair<32, 128, 32, 32, 256, 64, false>(MOE_FFN_ARGS);
+    launch_mfma_pair<32, 128, 32, 32, 256, 64>(MOE_FFN_ARGS);
   } else if (avg <= 64) {
-    launch_mfma_pair<64, 128, 64, 32, 256, 64, false>(MOE_FFN_ARGS);
+    launch_mfma_pair<64, 128, 64, 32, 256, 64>(MOE_FFN_ARGS);
   } else {
-    launch_mfma_pair<128, 64, 64, 32, 128, 64, false>(MOE_FFN_ARGS);
+    launch_mfma_pair<128, 64, 64, 32, 128, 64>(MOE_FFN_ARGS);
   }
 #undef MOE_FFN_ARGS
   return hipGetLastError();

@@ -39,16 +39,22 @@ static moe_status check_config(const moe_config* c) {
   return MOE_OK;
 }
 
+// Sizing calls pass a null base: pieces are then null too (no arithmetic on a
+// null pointer), only `bytes` is meaningful.
+template <typename T>
+static T* piece(void* ws, size_t off) {
+  return ws ? reinterpret_cast<T*>(static_cast<char*>(ws) + off) : nullptr;
+}
+
 RouteWs carve_route(void* ws, int T, int E) {
   RouteWs r;
-  char* p = static_cast<char*>(ws);
   size_t off = 0;
-  r.counters = reinterpret_cast<int32_t*>(p + off); off += kRouteCounterBytes;
-  r.logits = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * E * 4 * gate_split_cap(T, E));
-  r.xnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(T) * 4 * gate_split_cap(T, E));
-  r.wnorm2 = reinterpret_cast<float*>(p + off);     off += align_up(size_t(E) * 4);
-  r.recheck = reinterpret_cast<int32_t*>(p + off);  off += align_up(size_t(T) * 4);
-  r.recheck_low = reinterpret_cast<float*>(p + off); off += align_up(size_t(T) * 4);
+  r.counters = piece<int32_t>(ws, off);   off += kRouteCounterBytes;
+  r.logits = piece<float>(ws, off);       off += align_up(size_t(T) * E * 4 * gate_split_cap(T, E));
+  r.xnorm2 = piece<float>(ws, off);       off += align_up(size_t(T) * 4 * gate_split_cap(T, E));
+  r.wnorm2 = piece<float>(ws, off);       off += align_up(size_t(E) * 4);
+  r.recheck = piece<int32_t>(ws, off);    off += align_up(size_t(T) * 4);
+  r.recheck_low = piece<float>(ws, off);  off += align_up(size_t(T) * 4);
   r.bytes = off;
   return r;
 }
@@ -64,12 +70,11 @@ DispatchWs carve_dispatch(void* ws, int T, int k, int E_loc) {
 
 FfnWs carve_ffn(void* ws, int rows_capacity, int n_experts, int I_loc, int abytes) {
   FfnWs f;
-  char* p = static_cast<char*>(ws);
   f.max_tiles = rows_capacity / kMaxTileRows + n_experts + 1;
   size_t off = 0;
-  f.tiles = reinterpret_cast<int32_t*>(p + off); off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
-  f.tiles2 = reinterpret_cast<int32_t*>(p + off); off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
-  f.hmid = p + off;                              off += align_up(size_t(rows_capacity) * I_loc * abytes);
+  f.tiles = piece<int32_t>(ws, off);  off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
+  f.tiles2 = piece<int32_t>(ws, off); off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
+  f.hmid = piece<char>(ws, off);      off += align_up(size_t(rows_capacity) * I_loc * abytes);
   f.bytes = off;
   return f;
 }

@@ -146,6 +146,8 @@ class MoELayerShare:
             B.moe_quant_act(self.cfg, self.T, x, self.xq, self.xq_scales, stream)
         if concurrent:
             main = torch.cuda.current_stream() if stream is None else stream
+            if isinstance(main, int):                # a raw hipStream_t handle
+                main = torch.cuda.ExternalStream(main)
             self.side_stream.wait_stream(main)       # x ready; the previous combine has read shared_ys
             self.shared_ffn(x, self.side_stream, ws=self.ws_shared)
         if forced is None:

@@ -61,8 +61,10 @@ def check_routing(ids_gpu, w_gpu, ids_ref, w_ref, margin, scale, label=""):
 
 
 def check_dispatch(L, ids, w, x_np, want_rows=True):
-    """counts / offsets / perm / inv bit-exact against the oracle; xs rows are
-    bit copies."""
+    """counts / offsets / perm / inv bit-exact against the oracle; every valid
+    row of the send buffer is a bit copy of its token's row (compared on the
+    device in chunks, against the input rows gathered through the ORACLE's
+    permutation)."""
     c, o, perm, inv, _ = oracle.dispatch(ids, None, w.expert_lo, w.e_hi, want_xs=False)
     n = int(o[-1])
     assert np.array_equal(host(L.counts), c)
@@ -71,17 +73,64 @@ def check_dispatch(L, ids, w, x_np, want_rows=True):
     assert np.array_equal(host(L.inv), inv)
     if want_rows and n:
         k = w.k
-        rows = np.unique(np.concatenate([np.arange(min(n, 64)), np.arange(max(0, n - 64), n),
-                                         np.random.default_rng(1).integers(0, n, 256)]))
-        sel = torch.from_numpy(rows).to(L.xs.device)
-        if w.fp8_activations:      # dispatch copied the tokens' e4m3 codes and block scales
-            codes, scales = oracle.quant_act_1x128(x_np[perm[rows] // k])
-            got = host(L.xs_q[sel])
-            assert (((got == codes) | (((got | codes) & 0x7F) == 0))).all()
-            assert np.array_equal(host(L.xs_scales[:, sel]).T, scales)
+        device = L.perm.device
+        src = torch.from_numpy(perm // k).to(device)
+        if w.fp8_activations:
+            # dispatch copied the tokens' e4m3 codes and block scales: every row
+            # against the quantised token buffer, and that buffer against the
+            # oracle's quantiser on a spread of tokens
+            for lo in range(0, n, 1 << 16):
+                hi = min(n, lo + (1 << 16))
+                assert torch.equal(L.xs_q[lo:hi], L.xq[src[lo:hi]])
+                assert torch.equal(L.xs_scales[:, lo:hi], L.xq_scales[:, src[lo:hi]])
+            toks = np.unique(np.concatenate([np.arange(min(w.T, 64)), np.arange(max(0, w.T - 64), w.T),
+                                             np.random.default_rng(1).integers(0, w.T, 1024)]))
+            codes, scales = oracle.quant_act_1x128(x_np[toks])
+            sel = torch.from_numpy(toks).to(device)
+            got = host(L.xq[sel])
+            assert (((got == codes) | (((got | codes) & 0x7F) == 0))).all()      # +0 and -0 are one value
+            assert np.array_equal(host(L.xq_scales[:, sel]).T, scales)
         else:
-            assert np.array_equal(host(L.xs[sel]), x_np[perm[rows] // k])
+            xd = dev(x_np)
+            view = (lambda t: t.view(torch.int16)) if xd.dtype == torch.bfloat16 else (lambda t: t.view(torch.int32))
+            for lo in range(0, n, 1 << 16):
+                hi = min(n, lo + (1 << 16))
+                assert torch.equal(view(L.xs[lo:hi]), view(xd[src[lo:hi]])), "send-buffer rows %d..%d" % (lo, hi)
     return c, o, perm, inv
+
+
+def border_tokens(w, offsets, perm, at_least, seed=7):
+    """Tokens for a sampled output check at sizes where the oracle cannot do every
+    row: for every local expert the first and the last row of its segment and the
+    rows on either side of every possible M-tile border (tile heights are
+    multiples of 32 rows; segments longer than 1024 rows: the borders of the
+    balanced 160- and 256-row partitions and every multiple of 256), filled up
+    with random tokens to `at_least`."""
+    rows = set()
+    for e in range(len(offsets) - 1):
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        m = hi - lo
+        if m == 0:
+            continue
+        cuts = {0, m}
+        if m <= 1024:
+            cuts.update(range(32, m, 32))
+        else:
+            cuts.update(range(256, m, 256))
+            for bm in (160, 256):
+                nt = -(-m // bm)
+                step = -(-(-(-m // nt)) // 32) * 32
+                cuts.update(range(step, m, step))
+        for c in cuts:
+            if c > 0:
+                rows.add(lo + c - 1)
+            if c < m:
+                rows.add(lo + c)
+    toks = set((perm[np.array(sorted(rows), np.int64)] // w.k).tolist()) if rows else set()
+    rng = np.random.default_rng(seed)
+    while len(toks) < min(at_least, w.T):
+        toks.update(rng.integers(0, w.T, at_least).tolist())
+    return np.array(sorted(toks))
 
 
 def rel_err(a, ref):

@@ -334,6 +334,30 @@ def test_ffn_degenerate_loads(counts):
         assert rel_err(out[t:t + 1], one) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("rows_per_expert", [12, 13])
+def test_fp8_weights_on_both_sides_of_the_kernel_switch(rows_per_expert):
+    """e4m3 weights: up to twelve rows per expert (rows_capacity / n_experts) the
+    weight-streaming kernel applies the block scale to fp32 partial sums, above it
+    the tall-tile kernel rounds code * scale to bf16.  Both must meet the fp8
+    tolerance against the exact product on the same kind of load."""
+    E = 8
+    counts = [rows_per_expert] * E
+    counts[0] += 5                          # ragged, and one expert above the average
+    counts[3] -= 5
+    w, ids, tw = _forced_counts_case(counts, H=256, I=256, seed=23)
+    w = w.replace(weight_dtype="fp8", name="fp8_switch")
+    d = inputs(w)
+    L = make_layer(w, d)
+    out = host(L.forward(dev(d["x"]), (dev(ids), dev(tw))))
+    torch.cuda.synchronize()
+    assert w.T // E == rows_per_expert
+    check_dispatch(L, ids, w, d["x"])
+    ref, _ = oracle.layer_share(d["x"], ids, tw, 0, w.E, d["experts"])
+    err = rel_err(out, ref)
+    print("rows per expert", rows_per_expert, "err %.3e" % err, flush=True)
+    assert err <= TOL["fp8"]
+
+
 def _random_workload(seed):
     """A small layer with seeded random shape and gate options (every size a legal
     but awkward one: odd expert counts, k up to 8, ragged token counts, EP ranges)."""
