@@ -129,6 +129,27 @@ moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
                         void* stream);
 
 /*
+ * moe_dispatch for callers that cannot allocate or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  Same arguments, outputs and errors as moe_dispatch, minus the
+ * workspace: the index scratch (one int32 per local expert and sub-chunk of 64
+ * assignments, E_loc * ceil(T*k / 64) * 4 bytes) lives in a fixed device array
+ * inside the library, moe_dispatch_noalloc_max_bytes() = 4 MiB per GPU, held
+ * until the process ends.  A call whose scratch would exceed that returns
+ * MOE_ERR_WORKSPACE and enqueues nothing (the largest workload here, 65 536
+ * tokens x top-8 over 128 local experts, needs exactly 4 MiB).  The call
+ * allocates and frees nothing and synchronises nothing; the array's device
+ * address is looked up once per device on the first call there.  All calls on
+ * one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race and must be serialised by the caller; calls in
+ * stream order are safe, every call overwrites what it reads.
+ */
+size_t moe_dispatch_noalloc_max_bytes(void);
+moe_status moe_dispatch_noalloc(const moe_config* cfg, int32_t T, const void* x,
+                                const int32_t* topk_ids, int32_t* counts, int32_t* offsets,
+                                int32_t* perm, int32_t* inv, void* xs, void* stream);
+
+/*
  * Dispatch for the fused AG-Dispatch schedule (Alg. 2; Sec. III-C-2: hidden
  * states are replicated inside the MoE TP group, so they can be sharded there).
  * TP rank `tp_rank` of `tp_size` computes the expert map as moe_dispatch does

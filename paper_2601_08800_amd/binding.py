@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_PKG, "libmoe.so")
 _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatch",
+           "moe_dispatch_noalloc", "moe_dispatch_noalloc_max_bytes",
            "moe_dispatch_shard", "moe_expert_ffn", "moe_combine", "moe_combine_stage",
            "moe_fp8act_workspace_bytes", "moe_expert_ffn_fp8act", "moe_quant_act",
            "moe_dispatch_fp8q", "moe_expert_ffn_fp8q",
@@ -67,6 +68,10 @@ def load_library():
         lib.moe_route.argtypes = [cfgp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_dispatch.restype = ctypes.c_int
         lib.moe_dispatch.argtypes = [cfgp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.moe_dispatch_noalloc.restype = ctypes.c_int
+        lib.moe_dispatch_noalloc.argtypes = [cfgp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.moe_dispatch_noalloc_max_bytes.restype = sz
+        lib.moe_dispatch_noalloc_max_bytes.argtypes = []
         lib.moe_dispatch_shard.restype = ctypes.c_int
         lib.moe_dispatch_shard.argtypes = [cfgp, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.moe_combine_stage.restype = ctypes.c_int
@@ -148,6 +153,17 @@ def moe_dispatch(cfg, T, x, topk_ids, counts, offsets, perm, inv, xs, ws, stream
                                      _ws_bytes(ws) if ws_bytes is None else ws_bytes,
                                      _stream(stream))
     _check(st, "moe_dispatch")
+
+
+def moe_dispatch_noalloc_max_bytes() -> int:
+    return int(load_library().moe_dispatch_noalloc_max_bytes())
+
+
+def moe_dispatch_noalloc(cfg, T, x, topk_ids, counts, offsets, perm, inv, xs, stream=None):
+    st = load_library().moe_dispatch_noalloc(ctypes.byref(cfg), T, _ptr(x), _ptr(topk_ids),
+                                             _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv),
+                                             _ptr(xs), _stream(stream))
+    _check(st, "moe_dispatch_noalloc")
 
 
 def moe_dispatch_shard(cfg, T, x, topk_ids, tp_rank, tp_size, counts, offsets, perm, inv, xs_shard,

@@ -83,6 +83,34 @@ FfnWs carve_ffn(void* ws, int rows_capacity, int n_experts, int I_loc, int abyte
 
 using namespace moe;
 
+// ---- moe_dispatch_noalloc: the dispatch index scratch lives in the library ----
+// The multi-kernel dispatch keeps one count per (local expert, sub-chunk of 64
+// assignments) between its kernels.  For callers that cannot provide a workspace
+// this fixed device array stands in for it; each GPU the library runs on holds
+// its own copy at its own address until the process ends.
+constexpr size_t kNoAllocScratchBytes = size_t(4) << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+// Device address of `scratch` on the current device, resolved once per device
+// (the array's name is only a host-side handle for hipGetSymbolAddress; it is
+// never passed to a kernel or a runtime call as an address).
+static hipError_t noalloc_scratch(void** out) {
+  static void* ptr_of_device[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (!ptr_of_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr_of_device[dev] = p;
+  }
+  *out = ptr_of_device[dev];
+  return hipSuccess;
+}
+
 extern "C" {
 
 const char* moe_status_string(moe_status s) {
@@ -166,6 +194,25 @@ moe_status moe_dispatch(const moe_config* cfg, int32_t T, const void* x,
                         void* stream) {
   return dispatch_impl(cfg, T, x, topk_ids, 0, 1, counts, offsets, perm, inv, xs, ws, ws_bytes,
                        stream);
+}
+
+size_t moe_dispatch_noalloc_max_bytes(void) { return kNoAllocScratchBytes; }
+
+moe_status moe_dispatch_noalloc(const moe_config* cfg, int32_t T, const void* x,
+                                const int32_t* topk_ids, int32_t* counts, int32_t* offsets,
+                                int32_t* perm, int32_t* inv, void* xs, void* stream) {
+  moe_status st = check_config(cfg);
+  if (st != MOE_OK) return st;
+  if (T < 0) return MOE_ERR_INVALID_ARG;
+  if (T == 0) return MOE_OK;
+  if (size_t(T) * cfg->top_k > (size_t(1) << 30)) return MOE_ERR_UNSUPPORTED;
+  // the size limit is checked before anything touches the device
+  const size_t need = carve_dispatch(nullptr, T, cfg->top_k, cfg->expert_hi - cfg->expert_lo).bytes;
+  if (need > kNoAllocScratchBytes) return MOE_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (noalloc_scratch(&ws) != hipSuccess) return MOE_ERR_DEVICE;
+  return dispatch_impl(cfg, T, x, topk_ids, 0, 1, counts, offsets, perm, inv, xs, ws,
+                       kNoAllocScratchBytes, stream);
 }
 
 moe_status moe_dispatch_shard(const moe_config* cfg, int32_t T, const void* x,
