@@ -232,6 +232,15 @@ def measure(moe, name, steps, warmup, args, full):
         out["next_rows"] = next_rows(moe, L, w, x, a_loc, tokens_local, max(steps, 5))
         if forced is not None:
             out["route_separately"] = route_separately(moe, L, x, max(steps, 5))
+    # what the matrix units of this machine sustain with nothing else going on (a
+    # register-only MFMA loop, ~10 ms so that the clock settles): the power-limited
+    # ceiling of any bf16 GEMM here, beside the published peak the roofline is priced at
+    try:
+        tf = moe.moe_probe_mfma_rate(1024, 8000)
+        out["mfma_probe"] = {"TFLOPs": round(tf, 1), "frac_of_published_peak": round(tf / 2500.0, 4),
+                             "kernel": "register-only v_mfma_f32_32x32x16_bf16 loop, 1024 workgroups x 8 wavefronts"}
+    except Exception as exc:
+        out["mfma_probe"] = {"error": str(exc)[:200]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x_np, gate, experts, shared, forced_np,
                                            args.cpu_seconds)

@@ -262,6 +262,15 @@ moe_status moe_profile_filter(uint32_t mask);
  * MOE_K_COUNT entries), and clears the records (recording stays enabled). */
 moe_status moe_profile_read(double* total_ms, int32_t* launches);
 
+/* Calibration for the MFMA roofline (benchmark helper, not part of the layer):
+ * launches `workgroups` workgroups of eight wavefronts that do nothing but
+ * `iters` rounds of eight independent v_mfma_f32_32x32x16_bf16 on register
+ * operands, times the launch with an event pair on `stream`, waits for it, and
+ * returns the rate in TFLOP/s: what the matrix units of this machine sustain at
+ * the clock its power limit allows, with no loads, LDS traffic or barriers.
+ * Allocates no device memory; synchronises on its own events. */
+moe_status moe_probe_mfma_rate(int32_t workgroups, int32_t iters, void* stream, double* tflops);
+
 /* ---- expert FFN with 8-bit activations (an extension beyond the paper: both
  * GEMM operands e4m3, fp8 matrix instructions) --------------------------------
  * Same arguments and semantics as moe_expert_ffn for cfg->act_dtype = MOE_BF16,

@@ -19,7 +19,7 @@ EXPORTS = ("moe_workspace_bytes", "moe_status_string", "moe_route", "moe_dispatc
            "moe_fp8act_workspace_bytes", "moe_expert_ffn_fp8act", "moe_quant_act",
            "moe_dispatch_fp8q", "moe_expert_ffn_fp8q",
            "moe_profile_enable", "moe_profile_read",
-           "moe_profile_filter",
+           "moe_profile_filter", "moe_probe_mfma_rate",
            "moe_kernel_name")
 MOE_K_COUNT = 12
 
@@ -96,6 +96,8 @@ def load_library():
         lib.moe_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
         lib.moe_profile_filter.restype = ctypes.c_int
         lib.moe_profile_filter.argtypes = [ctypes.c_uint32]
+        lib.moe_probe_mfma_rate.restype = ctypes.c_int
+        lib.moe_probe_mfma_rate.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double)]
         lib.moe_kernel_name.restype = ctypes.c_char_p
         lib.moe_kernel_name.argtypes = [i32]
         _lib = lib
@@ -238,6 +240,14 @@ def moe_combine_stage(cfg, T, ys_block, inv, topk_w, tp_size, accumulate, out_bl
 
 def moe_profile_enable(max_records: int):
     _check(load_library().moe_profile_enable(max_records), "moe_profile_enable")
+
+
+def moe_probe_mfma_rate(workgroups: int, iters: int, stream=None) -> float:
+    """TFLOP/s of a register-only bf16 MFMA loop on this machine (calibration)."""
+    out = ctypes.c_double(0.0)
+    _check(load_library().moe_probe_mfma_rate(workgroups, iters, _stream(stream), ctypes.byref(out)),
+           "moe_probe_mfma_rate")
+    return out.value
 
 
 def moe_profile_filter(names=None):

@@ -56,6 +56,16 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 // tiles[0] = number of M tiles; then per tile a record (expert, first row, end
 // row, index of the expert's first tile, number of tiles of the expert).
 constexpr int kTileRec = 5;
+// K-split of leftover tiles (see ffn_gemm8w_kernel): at most this many tiles are
+// split, into at most kSplitMax parts of at least kSplitMinSteps K steps, and all
+// parts together are at most one workgroup per CU.
+constexpr int kCUs = 256;
+constexpr int kSplitTickets = 256;
+constexpr int kSplitMax = 4;
+constexpr int kSplitMinSteps = 24;
+constexpr int kPartFloats = 512 * 128;        // fp32 accumulators of one workgroup
+static_assert(kSplitTickets == kFfnSplitSlots && kCUs <= kFfnSplitSlots, "workspace holds one slot per part");
+static_assert(size_t(kPartFloats) * 4 == kFfnPartBytes, "partial-sum slot size");
 #ifndef MOE_SPREAD_SLOTS
 #define MOE_SPREAD_SLOTS 4
 #endif
@@ -68,9 +78,13 @@ __global__ __launch_bounds__(256) void ffn_tiles_kernel(const int32_t* __restric
                                                        int n_experts, int bm, int rows_capacity,
                                                        int32_t* __restrict__ tiles, int max_tiles,
                                                        int balance, int bm_second,
-                                                       int32_t* __restrict__ tiles_second) {
+                                                       int32_t* __restrict__ tiles_second,
+                                                       int32_t* __restrict__ tickets) {
   __shared__ int32_t start[513];
   __shared__ int32_t off[513];
+  // arrival counters of the K-split tiles of the two GEMM launches that follow
+  if (blockIdx.x == 0 && tickets)
+    for (int i = threadIdx.x; i < 2 * kSplitTickets; i += blockDim.x) tickets[i] = 0;
   // a second workgroup, when launched, builds a second table with its own tile height
   if (blockIdx.x == 1) {
     bm = bm_second;
@@ -317,6 +331,14 @@ __device__ __forceinline__ uint4 widen_scaled(uint2 c, float sc) {
   return r;
 }
 
+// One part of a K-split tile: `parts` workgroups share the tile's K range, part
+// `slot - slot0` of them is this one; parts == 1: the whole K range, no partial sums.
+struct SplitJob {
+  int parts, slot, slot0;
+  float* partial;          // [kCUs][kPartFloats]
+  int32_t* ticket;         // arrival counter of the tile
+};
+
 // F8: the weight tile holds e4m3 codes (64-byte rows: four pieces), widened to
 // bf16 on the way from LDS to the matrix unit.
 template <int NB, bool F8 = false> struct Ring {
@@ -345,7 +367,8 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
                                             const float* __restrict__ Se0,
                                             const float* __restrict__ Se1,
                                             uint16_t* __restrict__ C, int N, int K, int row0,
-                                            int row1, int n0, uint4* smem, int wave) {
+                                            int row1, int n0, uint4* smem, int wave, int kbeg,
+                                            int klen, const SplitJob& job) {
   constexpr int NBW = NB - WM * 4 < 0 ? 0 : (NB - WM * 4 > 4 ? 4 : NB - WM * 4);
   constexpr int SA = Ring<NB, F8>::kSA, SB = Ring<NB, F8>::kSB;
   constexpr int KS = Ring<NB, F8>::kBK;              // K step
@@ -360,7 +383,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   uint4* const ringB = smem + SA * AS;
   const int lane = threadIdx.x & 63;
   const int wn = wave & 3;
-  const int ksteps = K / KS;
+  const int ksteps = klen / KS;                      // this workgroup's K window starts at kbeg
 
   // LDS row r keeps its piece p at slot p ^ f(r): f = (r/2)&7 for 128-byte rows,
   // (r/4)&3 for 64-byte rows; both keep the 16 lanes the LDS serves per cycle
@@ -388,7 +411,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     const int piece = (lane % PPR) ^ ((rg * 4 + (lane >> 4)) & (PPR - 1));
     int r = row0 + rg * RPI + lrow;
     r = r < row1 ? r : row1 - 1;
-    asrc[q] = A + size_t(r) * K + piece * 8;
+    asrc[q] = A + size_t(r) * K + kbeg + piece * 8;
   }
 #pragma unroll
   for (int q = 0; q < NBQ; ++q) {
@@ -398,7 +421,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     const char* base = (DUAL && br >= 128) ? Be1 : Be0;
     int n = n0 + ((DUAL && br >= 128) ? br - 128 : br);
     n = n < N ? n : N - 1;
-    bsrc[q] = base + (size_t(n) * K) * WB + piece * 16;
+    bsrc[q] = base + (size_t(n) * K + kbeg) * WB + piece * 16;
   }
   const bool extra = AREM > 0 && wave < AREM;        // this wavefront loads one more A row group
   auto issue_a = [&](int ks) {
@@ -568,6 +591,68 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   for (; ks < ksteps; ++ks) turn(ks, std::false_type{});
   if constexpr (NBW > 0) mfmas(1);                           // sub-step 3 of the last step
 
+  // A K-split part leaves its fp32 accumulators in the workspace (register order:
+  // 8-byte chunk c of thread t at index c*512 + t, so a wavefront's store is 512
+  // contiguous bytes); the part that arrives last adds all parts in the
+  // order of their K windows and carries on with the epilogue.  No workgroup waits
+  // for another: every part counts itself in and all but the last one leave.
+  if (job.parts > 1) {
+    // The partial sums go past the XCD's own (non-coherent) L2 as device-scope
+    // stores and are read back as device-scope loads, so no cache has to be
+    // written back or invalidated as a whole; the wait below makes every store of
+    // this part complete before the part counts itself in.
+    uint64_t* const mine = reinterpret_cast<uint64_t*>(job.partial + size_t(job.slot) * kPartFloats) + threadIdx.x;
+    if constexpr (NBW > 0) {
+#pragma unroll
+      for (int i = 0; i < NBW; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const uint64_t bits = uint64_t(__float_as_uint(acc[i][j][2 * q])) |
+                                  (uint64_t(__float_as_uint(acc[i][j][2 * q + 1])) << 32);
+            __hip_atomic_store(mine + ((i * 2 + j) * 8 + q) * 512, bits, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+          }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int32_t* const flag = reinterpret_cast<int32_t*>(smem);   // the rings are idle from here on
+    if (threadIdx.x == 0) *flag = atomicAdd(job.ticket, 1);
+    __syncthreads();
+    if (*flag != job.parts - 1) return;
+    if constexpr (NBW > 0) {
+      // one 32x32 block at a time: its chunks of all (at most four) parts are
+      // fetched together, then added in the order of the parts
+      const uint64_t* const all = reinterpret_cast<const uint64_t*>(job.partial + size_t(job.slot0) * kPartFloats) + threadIdx.x;
+#pragma unroll
+      for (int i = 0; i < NBW; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          uint64_t v[kSplitMax][8];
+#pragma unroll
+          for (int p = 0; p < kSplitMax; ++p)
+            if (p < job.parts) {
+#pragma unroll
+              for (int q = 0; q < 8; ++q)
+                v[p][q] = __hip_atomic_load(all + size_t(p) * (kPartFloats / 2) + ((i * 2 + j) * 8 + q) * 512,
+                                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+#pragma unroll
+          for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+#pragma unroll
+          for (int p = 0; p < kSplitMax; ++p)
+            if (p < job.parts) {
+#pragma unroll
+              for (int q = 0; q < 8; ++q) {
+                acc[i][j][2 * q] += __uint_as_float(uint32_t(v[p][q]));
+                acc[i][j][2 * q + 1] += __uint_as_float(uint32_t(v[p][q] >> 32));
+              }
+            }
+        }
+    }
+  }
+
   // Epilogue.  Lane l holds column l%32 of each 32x32 block and rows
   // (q/4)*8 + (l/32)*4 + q%4: two rows are rounded to bf16 by one packed convert
   // and stored as the low / high half.  Only the last 32-row block of a tile can
@@ -614,24 +699,63 @@ template <bool DUAL, int NB, bool F8>
 __device__ __forceinline__ void gemm8w_tile(const uint16_t* A, const char* Be0, const char* Be1,
                                             const float* Se0, const float* Se1, uint16_t* C, int N,
                                             int K, int row0, int row1, int n0, uint4* smem,
-                                            int wave) {
-  if (wave < 4) gemm8w_body<DUAL, NB, 0, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave);
-  else gemm8w_body<DUAL, NB, 1, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave);
+                                            int wave, int kbeg, int klen, const SplitJob& job) {
+  if (wave < 4) gemm8w_body<DUAL, NB, 0, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kbeg, klen, job);
+  else gemm8w_body<DUAL, NB, 1, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kbeg, klen, job);
 }
 
+// Leftover tiles.  The hardware hands workgroups to CUs in the order of their
+// ids, so when the number of tiles is not a multiple of the 256 CUs the last
+// `left` tiles run on `left` CUs while the rest idle for a whole tile time.  When
+// at most half of the CUs would be busy, those tiles are cut along K into `parts`
+// workgroups each (parts * left <= 256), placed at the end of the grid; everything
+// is derived from the tile count on the device, so there is no host round trip.
+// The same rule spreads a launch of a few tiles (a shared expert at a decode
+// batch) over the chip.
 template <bool DUAL, bool F8>
 __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
     const uint16_t* __restrict__ A, const void* __restrict__ B0, const void* __restrict__ B1,
     const float* __restrict__ S0, const float* __restrict__ S1, uint16_t* __restrict__ C, int N,
-    int K, const int32_t* __restrict__ tiles, int m_fastest) {
+    int K, const int32_t* __restrict__ tiles, int m_fastest, float* __restrict__ partial,
+    int32_t* __restrict__ tickets) {
   constexpr int BN = DUAL ? 128 : 256;
   extern __shared__ uint4 smem[];
   const int n_ntiles = (N + BN - 1) / BN;
   const int total = tiles[0] * n_ntiles;
-  const int per_xcd = (total + 7) >> 3;
+  const int ksteps_all = K / 64;
   const int pid = blockIdx.x;
-  const int logical = (pid & 7) * per_xcd + (pid >> 3);
-  if ((pid >> 3) >= per_xcd || logical >= total) return;
+  const int left = total % kCUs;
+  int parts = 1;
+  if (partial && left > 0 && left <= kCUs / 2) {
+    parts = kCUs / left;
+    parts = parts < kSplitMax ? parts : kSplitMax;
+    const int cap = ksteps_all / kSplitMinSteps;
+    parts = parts < cap ? parts : cap;
+  }
+  int logical, part = 0;
+  SplitJob job{1, 0, 0, partial, tickets};
+  if (parts >= 2) {
+    // whole rounds first, every XCD walking a contiguous run of their tiles, then
+    // the parts of the leftover tiles
+    const int full = total - left;
+    if (pid < full) {
+      logical = (pid & 7) * (full >> 3) + (pid >> 3);
+    } else {
+      const int q = pid - full;
+      if (q >= left * parts) return;
+      const int j = q / parts;
+      part = q - j * parts;
+      logical = full + j;
+      job.parts = parts;
+      job.slot = q;
+      job.slot0 = j * parts;
+      job.ticket = tickets + j;
+    }
+  } else {
+    const int per_xcd = (total + 7) >> 3;
+    logical = (pid & 7) * per_xcd + (pid >> 3);
+    if ((pid >> 3) >= per_xcd || logical >= total) return;
+  }
   int mtile = logical / n_ntiles, ntile = logical - mtile * n_ntiles;
   if (m_fastest) {
     // Inside an expert's block of tiles: groups of up to four M tiles; per group
@@ -642,14 +766,20 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
     const int local = logical - first * n_ntiles;
     const int gsz = 4 * n_ntiles;
     const int grp = local / gsz, rem = local - grp * gsz;
-    const int left = cnt - grp * 4;
-    const int mc = left < 4 ? left : 4;
+    const int left_m = cnt - grp * 4;
+    const int mc = left_m < 4 ? left_m : 4;
     ntile = rem / mc;
     mtile = first + grp * 4 + (rem - ntile * mc);
   }
   const int e = tiles[1 + kTileRec * mtile], row0 = tiles[2 + kTileRec * mtile],
             row1 = tiles[3 + kTileRec * mtile];
   const int n0 = ntile * BN;
+  // this workgroup's window of K steps (even bounds: a block scale spans two steps)
+  int kb = 0, ke = ksteps_all;
+  if (job.parts > 1) {
+    kb = (part * ksteps_all / job.parts) & ~1;
+    ke = part == job.parts - 1 ? ksteps_all : (((part + 1) * ksteps_all / job.parts) & ~1);
+  }
   constexpr int WB = F8 ? 1 : 2;
   const char* Be0 = static_cast<const char*>(B0) + size_t(e) * N * K * WB;
   const char* Be1 = DUAL ? static_cast<const char*>(B1) + size_t(e) * N * K * WB : nullptr;
@@ -661,11 +791,12 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
     const int nkb = K / 128, nnb = N / 128;
     int nb = (n0 + (wave & 3) * (DUAL ? 32 : 64)) / 128;
     nb = nb < nnb ? nb : nnb - 1;
-    Se0 = S0 + (size_t(e) * nnb + nb) * nkb;
-    Se1 = DUAL ? S1 + (size_t(e) * nnb + nb) * nkb : Se0;
+    Se0 = S0 + (size_t(e) * nnb + nb) * nkb + (kb >> 1);
+    Se1 = DUAL ? S1 + (size_t(e) * nnb + nb) * nkb + (kb >> 1) : Se0;
   }
-#define MOE_TILE_(NBV) \
-  gemm8w_tile<DUAL, NBV, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave)
+#define MOE_TILE_(NBV)                                                                        \
+  gemm8w_tile<DUAL, NBV, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kb * 64, \
+                             (ke - kb) * 64, job)
   switch ((row1 - row0 + 31) >> 5) {     // valid 32-row blocks of the tile
     case 1: MOE_TILE_(1); break;
     case 2: MOE_TILE_(2); break;
@@ -929,7 +1060,7 @@ void launch_mfma_pair(const moe_config& c, int n_experts, const void* xs, const 
   const int max_mt = rows_capacity / BM + n_experts;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
                      rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0, 0,
-             (int32_t*)nullptr);
+             (int32_t*)nullptr, (int32_t*)nullptr);
   const int nt1 = (I + BN1 - 1) / BN1, nt2 = (H + BN2 - 1) / BN2;
   auto k1 = ffn_gemm_kernel<BM, BN1, WM, WN1, true>;
   auto k2 = ffn_gemm_kernel<BM, BN2, WM, WN2, false>;
@@ -954,7 +1085,7 @@ void launch_skinny(const moe_config& c, int n_experts, const void* xs, const int
   const int max_mt = rows_capacity / 32 + n_experts;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, 32,
              rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0, 0,
-             (int32_t*)nullptr);
+             (int32_t*)nullptr, (int32_t*)nullptr);
   const int nt1 = (I + 31) / 32, nt2 = (H + 63) / 64;
   MOE_LAUNCH(MOE_K_FFN_GEMM1, (ffn_skinny_kernel<true, FP8>), dim3(size_t(max_mt) * nt1), dim3(256),
              0, s, static_cast<const uint16_t*>(xs), w_gate, w_up, s_gate, s_up,
@@ -982,20 +1113,23 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   const int cap = max_mt < ws.max_tiles ? max_mt : ws.max_tiles;
   int32_t* const tiles2 = bm2 == bm ? ws.tiles : ws.tiles2;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(bm2 == bm ? 1 : 2), dim3(256), 0, s, offsets,
-             n_experts, bm, rows_capacity, ws.tiles, cap, 1, bm2, tiles2);
+             n_experts, bm, rows_capacity, ws.tiles, cap, 1, bm2, tiles2, ws.tickets);
   const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
   constexpr int lds = 160 * 1024;         // all of a CU's LDS: the rings of the tallest tile fill it
-  const int g1 = (max_mt * nt1 + 7) / 8 * 8, g2 = (max_mt2 * nt2 + 7) / 8 * 8;
+  // room for the parts of the leftover tiles behind the whole tiles
+  const int g1 = (max_mt * nt1 + 7) / 8 * 8 + kCUs, g2 = (max_mt2 * nt2 + 7) / 8 * 8 + kCUs;
   auto k1 = ffn_gemm8w_kernel<true, F8>;
   auto k2 = ffn_gemm8w_kernel<false, F8>;
   static uint64_t opted1 = 0, opted2 = 0;
   lds_opt_in(reinterpret_cast<const void*>(k1), lds, opted1);
   lds_opt_in(reinterpret_cast<const void*>(k2), lds, opted2);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
-             w_gate, w_up, s_gate, s_up, static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
+             w_gate, w_up, s_gate, s_up, static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1,
+             ws.partial, ws.tickets);
   MOE_LAUNCH(MOE_K_FFN_GEMM2, k2, dim3(g2), dim3(512), lds, s,
              static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr, s_down,
-             (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, tiles2, 1);
+             (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, tiles2, 1, ws.partial,
+             ws.tickets + kSplitTickets);
 }
 
 // Between the two: a handful of rows per expert.  GEMM-1 (K = H long) streams its
@@ -1013,15 +1147,16 @@ void launch_mixed(const moe_config& c, int n_experts, const void* xs, const int3
   const int max_mt2 = rows_capacity / bm2 + n_experts;
   const int cap = max_mt2 < ws.max_tiles ? max_mt2 : ws.max_tiles;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(2), dim3(256), 0, s, offsets, n_experts, bm,
-             rows_capacity, ws.tiles, cap, 1, bm2, ws.tiles2);
+             rows_capacity, ws.tiles, cap, 1, bm2, ws.tiles2, ws.tickets);
   const int nt1 = (I + 127) / 128, nt2 = (H + 63) / 64;
   constexpr int lds = 160 * 1024;
-  const int g1 = (max_mt * nt1 + 7) / 8 * 8;
+  const int g1 = (max_mt * nt1 + 7) / 8 * 8 + kCUs;
   auto k1 = ffn_gemm8w_kernel<true, F8>;
   static uint64_t opted1 = 0;
   lds_opt_in(reinterpret_cast<const void*>(k1), lds, opted1);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
-             w_gate, w_up, s_gate, s_up, static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1);
+             w_gate, w_up, s_gate, s_up, static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1,
+             ws.partial, ws.tickets);
   MOE_LAUNCH(MOE_K_FFN_GEMM2, (ffn_skinny_kernel<false, F8>), dim3(size_t(max_mt2) * nt2), dim3(256),
              0, s, static_cast<const uint16_t*>(ws.hmid), w_down, (const void*)nullptr, s_down,
              (const float*)nullptr, static_cast<uint16_t*>(ys), H, I, ws.tiles2);
@@ -1040,7 +1175,7 @@ hipError_t launch_expert_ffn(const moe_config& c, int n_experts, const void* xs,
     const int max_mt = rows_capacity / BM + n_experts;
     MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(1), dim3(256), 0, s, offsets, n_experts, BM,
                        rows_capacity, ws.tiles, max_mt < ws.max_tiles ? max_mt : ws.max_tiles, 0, 0,
-             (int32_t*)nullptr);
+             (int32_t*)nullptr, (int32_t*)nullptr);
     MOE_LAUNCH(MOE_K_FFN_GEMM1, ffn_f32_kernel<true>, dim3(size_t(max_mt) * ((I + 63) / 64)), dim3(256), 0,
                        s, static_cast<const float*>(xs), static_cast<const float*>(w_gate),
                        static_cast<const float*>(w_up), static_cast<float*>(ws.hmid), I, H,

@@ -52,7 +52,7 @@ RouteWs carve_route(void* ws, int T, int E) {
   r.counters = piece<int32_t>(ws, off);   off += kRouteCounterBytes;
   r.logits = piece<float>(ws, off);       off += align_up(size_t(T) * E * 4 * gate_split_cap(T, E));
   r.xnorm2 = piece<float>(ws, off);       off += align_up(size_t(T) * 4 * gate_split_cap(T, E));
-  r.wnorm2 = piece<float>(ws, off);       off += align_up(size_t(E) * 4);
+  r.wnorm2 = piece<float>(ws, off);       off += align_up(size_t(E) * 4 * gate_split_cap(T, E));
   r.recheck = piece<int32_t>(ws, off);    off += align_up(size_t(T) * 4);
   r.recheck_low = piece<float>(ws, off);  off += align_up(size_t(T) * 4);
   r.bytes = off;
@@ -75,6 +75,8 @@ FfnWs carve_ffn(void* ws, int rows_capacity, int n_experts, int I_loc, int abyte
   f.tiles = piece<int32_t>(ws, off);  off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
   f.tiles2 = piece<int32_t>(ws, off); off += align_up(size_t(1 + 5 * f.max_tiles) * 4 + 12);
   f.hmid = piece<char>(ws, off);      off += align_up(size_t(rows_capacity) * I_loc * abytes);
+  f.tickets = piece<int32_t>(ws, off); off += align_up(size_t(2) * kFfnSplitSlots * 4);
+  f.partial = piece<float>(ws, off);   off += align_up(size_t(kFfnSplitSlots) * kFfnPartBytes);
   f.bytes = off;
   return f;
 }

@@ -30,12 +30,15 @@ inline int gate_split_cap(int T, int E) {
   while (n < kGateMaxSplit && blocks * n * 2 <= kGateWgTarget) n *= 2;
   return n < 2 ? 2 : n;
 }
-constexpr int kGateChainSteps = 1;            // K-steps of 64 per fp32 accumulation chain
+#ifndef MOE_GATE_CHAIN
+#define MOE_GATE_CHAIN 1
+#endif
+constexpr int kGateChainSteps = MOE_GATE_CHAIN;   // K-steps of 64 per fp32 accumulation chain
 struct RouteWs {
   int32_t* counters;   // [64]
   float* logits;       // [gate_split_cap][T,E] fast logits (fp32), one slab per K split
   float* xnorm2;       // [gate_split_cap][T] sum of squares of the token row, per K split
-  float* wnorm2;       // [E] sum of squares of the gate row
+  float* wnorm2;       // [gate_split_cap][E] sum of squares of the gate row, per K split
   int32_t* recheck;    // [T] token ids to re-score
   float* recheck_low;  // [T] per listed token: smallest lower bound of its picks (NaN: not known)
   size_t bytes;
@@ -55,10 +58,14 @@ DispatchWs carve_dispatch(void* ws, int T, int k, int E_loc);
 
 // expert FFN
 constexpr int kMaxTileRows = 32;              // smallest M tile any FFN kernel uses
+constexpr int kFfnSplitSlots = 256;           // K-split parts in flight: one workgroup per CU at most
+constexpr size_t kFfnPartBytes = size_t(512) * 128 * 4;   // fp32 accumulators of one workgroup
 struct FfnWs {
   int32_t* tiles;      // [0]=number of M tiles, then 5-int tile records
   int32_t* tiles2;     // a second table of the same capacity (GEMM-2 with another tile height)
   void* hmid;          // [rows_capacity, I_loc] act dtype
+  float* partial;      // fp32 partial sums of K-split tiles: kFfnSplitSlots workgroups' accumulators
+  int32_t* tickets;    // [2 * kFfnSplitSlots] arrival counters of the split tiles (GEMM-1, GEMM-2)
   int max_tiles;
   size_t bytes;
 };

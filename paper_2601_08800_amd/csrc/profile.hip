@@ -28,6 +28,43 @@ void prof_mark(int kernel_id, hipStream_t s, bool begin) {
   }
 }
 
+// ---- calibration: the matrix units with nothing else going on ---------------
+// Every wavefront runs `iters` rounds of eight independent
+// v_mfma_f32_32x32x16_bf16 on register operands (128 accumulator registers, two
+// wavefronts per SIMD: the shape of the tall-tile GEMM's inner loop without its
+// loads, LDS reads and barriers).  Operands are non-trivial bit patterns so that
+// the data path toggles as it does on real inputs.  Nothing is stored unless
+// `sink` is given.
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(512) void mfma_probe_kernel(int iters, float* sink) {
+  const uint32_t h = (threadIdx.x * 2654435761u) ^ (blockIdx.x * 40503u);
+  // bf16 values of magnitude 0.5 .. 1 with hashed signs and mantissas
+  const uint32_t pat = 0x3f003f00u | (h & 0x807f807fu);
+  uint4 ua = make_uint4(pat, pat ^ 0x80000040u, pat ^ 0x00408000u, pat ^ 0x80108010u);
+  uint4 ub = make_uint4(pat ^ 0x00208020u, pat ^ 0x80400000u, pat ^ 0x00008008u, pat ^ 0x80048004u);
+  probe_f32x16 acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[j][q] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+    const probe_bf16x8 a = __builtin_bit_cast(probe_bf16x8, ua), b = __builtin_bit_cast(probe_bf16x8, ub);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+    ua.x ^= 0x80008000u;          // keep the sums from drifting: alternate the sign of one pair
+  }
+  if (sink) {
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) s += acc[j][q];
+    sink[blockIdx.x * 512 + threadIdx.x] = s;
+  }
+}
+
 }  // namespace moe
 
 using namespace moe;
@@ -75,6 +112,26 @@ moe_status moe_profile_read(double* total_ms, int32_t* launches) {
     launches[g_pool[i].id] += 1;
   }
   g_used = 0;
+  return MOE_OK;
+}
+
+moe_status moe_probe_mfma_rate(int32_t workgroups, int32_t iters, void* stream, double* tflops) {
+  if (workgroups < 1 || workgroups > (1 << 20) || iters < 1 || !tflops) return MOE_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return MOE_ERR_DEVICE;
+  if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return MOE_ERR_DEVICE;}
+  float ms = 0.f;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(workgroups), dim3(512), 0, s, iters / 8 + 1, (float*)nullptr);  // warm-up
+  bool ok = hipEventRecord(a, s) == hipSuccess;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(workgroups), dim3(512), 0, s, iters, (float*)nullptr);
+  ok = ok && hipGetLastError() == hipSuccess && hipEventRecord(b, s) == hipSuccess &&
+       hipEventSynchronize(b) == hipSuccess && hipEventElapsedTime(&ms, a, b) == hipSuccess;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  if (!ok || ms <= 0.f) return MOE_ERR_DEVICE;
+  // 8 wavefronts x iters x 8 instructions x 32*32*16*2 flops
+  *tflops = double(workgroups) * 8.0 * iters * 8.0 * 32768.0 / (ms * 1e-3) / 1e12;
   return MOE_OK;
 }
 

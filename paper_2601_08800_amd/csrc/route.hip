@@ -136,6 +136,18 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) {
   return __uint_as_float(hi16 << 16);
 }
 
+// Sum of squares of the eight bf16 values of a 16-byte piece, added to acc (fp32).
+__device__ __forceinline__ float piece_sumsq(const uint4& a, float acc) {
+  const uint32_t v[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const float lo = bf16_bits_to_f32(v[q] & 0xffffu), hi = bf16_bits_to_f32(v[q] >> 16);
+    acc = fmaf(lo, lo, acc);
+    acc = fmaf(hi, hi, acc);
+  }
+  return acc;
+}
+
 // fp64 dot product of two 16-byte pieces (8 bf16 or 4 fp32), added to acc.
 template <bool BF16>
 __device__ __forceinline__ double piece_dot64(const uint4& a, const uint4& b, double acc) {
@@ -248,7 +260,9 @@ template <int CHAIN_STEPS>
 __global__ __launch_bounds__(512) void gate_mfma_kernel(const uint16_t* __restrict__ x,
                                                         const uint16_t* __restrict__ gate_w, int T,
                                                         int H, int E, float* __restrict__ logits,
-                                                        float* __restrict__ xnorm2) {
+                                                        float* __restrict__ xnorm2,
+                                                        float* __restrict__ wnorm2,
+                                                        int32_t* __restrict__ counters) {
   __shared__ uint4 As[2][GBM * 8];
   __shared__ uint4 Bs[2][GBN * 8];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -260,11 +274,13 @@ __global__ __launch_bounds__(512) void gate_mfma_kernel(const uint16_t* __restri
   const int ksteps = (ks0 + per_split < all_steps ? ks0 + per_split : all_steps) - ks0;
   logits += size_t(blockIdx.z) * T * E;
   xnorm2 += size_t(blockIdx.z) * T;
+  wnorm2 += size_t(blockIdx.z) * E;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid < 64) counters[tid] = 0;
 
   // global -> register staging: A 1 piece / thread, B 2 pieces / thread
   const int lrow = tid >> 3, lpiece = tid & 7;        // lrow 0..63
   uint4 ra, rb[2];
-  float xsq = 0.f;
+  float xsq = 0.f, wsq[2] = {0.f, 0.f};
   auto gload = [&](int ks) {
     const int kcol = (ks0 + ks) * GBK + lpiece * 8;
     const bool kin = kcol < H;
@@ -289,6 +305,10 @@ __global__ __launch_bounds__(512) void gate_mfma_kernel(const uint16_t* __restri
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i) Bs[buf][swz(lrow + 64 * i, lpiece)] = rb[i];
+    if (blockIdx.x == 0) {                            // the first token tile also sums the gate rows' squares
+#pragma unroll
+      for (int i = 0; i < 2; ++i) wsq[i] = piece_sumsq(rb[i], wsq[i]);
+    }
   };
 
   f32x16 acc;
@@ -334,6 +354,17 @@ __global__ __launch_bounds__(512) void gate_mfma_kernel(const uint16_t* __restri
     const int r = m0 + lrow;
     if (lpiece == 0 && r < T) xnorm2[r] = s * 1.001f;
   }
+  if (blockIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      float s = wsq[i];
+      s += __shfl_xor(s, 1);
+      s += __shfl_xor(s, 2);
+      s += __shfl_xor(s, 4);
+      const int n = n0 + lrow + 64 * i;
+      if (lpiece == 0 && n < E) wnorm2[n] = s * 1.001f;
+    }
+  }
 }
 
 // The gate GEMM with the operands brought global -> LDS directly
@@ -357,7 +388,9 @@ template <int BM, int NS, int CHAIN_STEPS>
 __device__ __forceinline__ void gate_dma_body(const uint16_t* __restrict__ x,
                                               const uint16_t* __restrict__ gate_w, int T, int H,
                                               int E, float* __restrict__ logits,
-                                              float* __restrict__ xnorm2, uint4* smem) {
+                                              float* __restrict__ xnorm2,
+                                              float* __restrict__ wnorm2,
+                                              int32_t* __restrict__ counters, uint4* smem) {
   constexpr int MW = BM / 32;                // wavefronts along M
   constexpr int NT = (GBN / 32) * MW / 8;    // MFMA tiles (32 experts each) per wavefront
   constexpr int NA = BM / 64;                // A load instructions per thread and step
@@ -373,6 +406,8 @@ __device__ __forceinline__ void gate_dma_body(const uint16_t* __restrict__ x,
   const int ksteps = (ks0 + per_split < all_steps ? ks0 + per_split : all_steps) - ks0;
   logits += size_t(blockIdx.z) * T * E;
   xnorm2 += size_t(blockIdx.z) * T;
+  wnorm2 += size_t(blockIdx.z) * E;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid < 64) counters[tid] = 0;
 
   // this thread's slots: tid + 512 i of the A stage (i < NA) and of the B stage (i < 2);
   // rows lrow + 64 i, and (lrow + 64 i) / 2 & 7 does not depend on i
@@ -409,7 +444,7 @@ __device__ __forceinline__ void gate_dma_body(const uint16_t* __restrict__ x,
   for (int j = 0; j < NT; ++j)
 #pragma unroll
     for (int i = 0; i < 16; ++i) { acc[j][i] = 0.f; dsum[j][i] = 0.0; }
-  float xsq[NA];
+  float xsq[NA], wsq[2] = {0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < NA; ++i) xsq[i] = 0.f;
 
@@ -437,16 +472,11 @@ __device__ __forceinline__ void gate_dma_body(const uint16_t* __restrict__ x,
     }
     if (blockIdx.y == 0) {                        // squared row norms from this thread's own pieces
 #pragma unroll
-      for (int i = 0; i < NA; ++i) {
-        const uint4 va = Ast[tid + 512 * i];
-        const uint32_t v[4] = {va.x, va.y, va.z, va.w};
+      for (int i = 0; i < NA; ++i) xsq[i] = piece_sumsq(Ast[tid + 512 * i], xsq[i]);
+    }
+    if (blockIdx.x == 0) {                        // the first token tile also sums the gate rows' squares
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float lo = bf16_bits_to_f32(v[q] & 0xffffu), hi = bf16_bits_to_f32(v[q] >> 16);
-          xsq[i] = fmaf(lo, lo, xsq[i]);
-          xsq[i] = fmaf(hi, hi, xsq[i]);
-        }
-      }
+      for (int i = 0; i < 2; ++i) wsq[i] = piece_sumsq(Bst[tid + 512 * i], wsq[i]);
     }
     if ((ks + 1) % CHAIN_STEPS == 0 || ks + 1 == ksteps) {
 #pragma unroll
@@ -477,19 +507,32 @@ __device__ __forceinline__ void gate_dma_body(const uint16_t* __restrict__ x,
       if ((tid & 7) == 0 && r < T) xnorm2[r] = s * 1.001f;
     }
   }
+  if (blockIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      float s = wsq[i];
+      s += __shfl_xor(s, 1);
+      s += __shfl_xor(s, 2);
+      s += __shfl_xor(s, 4);
+      const int n = n0 + lrow + 64 * i;
+      if ((tid & 7) == 0 && n < E) wnorm2[n] = s * 1.001f;
+    }
+  }
 }
 
 template <int BM, int NS, int CHAIN_STEPS>
 __global__ __launch_bounds__(512) void gate_dma_kernel(const uint16_t* __restrict__ x,
                                                        const uint16_t* __restrict__ gate_w, int T,
                                                        int H, int E, float* __restrict__ logits,
-                                                       float* __restrict__ xnorm2) {
+                                                       float* __restrict__ xnorm2,
+                                                       float* __restrict__ wnorm2,
+                                                       int32_t* __restrict__ counters) {
   extern __shared__ uint4 gate_smem[];
   // The ring is handed on as a generic pointer: with the LDS array named in the
   // loop the compiler puts a vmcnt(0) in front of every LDS read that follows a
   // DMA in program order, which would drain the ring; the waits and the barrier
   // in the body order the DMA writes and the reads explicitly.
-  gate_dma_body<BM, NS, CHAIN_STEPS>(x, gate_w, T, H, E, logits, xnorm2, gate_smem);
+  gate_dma_body<BM, NS, CHAIN_STEPS>(x, gate_w, T, H, E, logits, xnorm2, wnorm2, counters, gate_smem);
 }
 
 // ----------------------------------------------------------- stage 2: select
@@ -499,6 +542,7 @@ struct SelCfg {
   float chain_err;   // 2n * 2^-24 of the gate accumulation (0 when logits are given)
   int have_norms;
   int nsplit;        // K splits of the gate GEMM: logits and row norms are sums of this many slabs
+  int wsplit;        // slabs of the gate rows' sums of squares (stride E)
   int T;             // tokens: slab strides are T*E (logits) and T (row norms)
 };
 
@@ -508,6 +552,39 @@ __device__ __forceinline__ float token_norm(const SelCfg& c, const float* __rest
   float s = xnorm2[t];
   for (int i = 1; i < c.nsplit; ++i) s += xnorm2[t + size_t(i) * c.T];
   return sqrtf(s);
+}
+
+// Norm of gate row e from the per-split sums of squares.
+__device__ __forceinline__ float gate_norm(const SelCfg& c, const float* __restrict__ wnorm2, int e) {
+  float s = wnorm2[e];
+  for (int i = 1; i < c.wsplit; ++i) s += wnorm2[e + i * c.E];
+  return sqrtf(s);
+}
+
+// Fast key of one expert from its stage-1 logit z (the slabs already added up):
+// key, the bound eps on |key - exact key|, and the value sc the weight is made of.
+// wn = norm of the gate row (unused without norms).
+__device__ __forceinline__ void fast_key_one(const SelCfg& c, float z, float xn, float wn,
+                                             const float* __restrict__ logit_bias,
+                                             const float* __restrict__ select_bias, int e,
+                                             float& key, float& eps, float& sc) {
+  float ez = 0.f;
+  if (c.have_norms) ez = c.chain_err * xn * wn * 1.001f + 2.f * kUlp * fabsf(z);
+  if (logit_bias) {
+    z += logit_bias[e];
+    ez += kUlp * fabsf(z);
+  }
+  if (c.score_fn == MOE_SCORE_SOFTMAX) {
+    key = z; eps = ez; sc = z;
+  } else {
+    const float s = 1.0f / (1.0f + expf(-z));
+    const float sb = select_bias ? select_bias[e] : 0.f;
+    key = s + sb;
+    sc = s;
+    // |sigmoid(z+d)-sigmoid(z)| <= s(1-s)|d| + d^2/16 ; fp32 evaluation of
+    // the sigmoid and of the bias add is good to a few ulp of 1+|sb|
+    eps = ez * (s * (1.f - s) + ez + 16.f * kUlp) + 16.f * kUlp * (1.f + fabsf(sb));
+  }
 }
 
 // Per-lane view of one token's experts: expert e = slot*64 + lane.
@@ -548,23 +625,8 @@ __device__ __forceinline__ void fast_keys(const SelCfg& c, const float* __restri
     if (e < c.E) {
       float z = logits_row[e];
       for (int sp = 1; sp < c.nsplit; ++sp) z += logits_row[e + size_t(sp) * c.T * c.E];
-      float ez = 0.f;
-      if (c.have_norms) ez = c.chain_err * xn * sqrtf(wnorm2[e]) * 1.001f + 2.f * kUlp * fabsf(z);
-      if (logit_bias) {
-        z += logit_bias[e];
-        ez += kUlp * fabsf(z);
-      }
-      if (c.score_fn == MOE_SCORE_SOFTMAX) {
-        key = z; eps = ez; sc = z;
-      } else {
-        const float s = 1.0f / (1.0f + expf(-z));
-        const float sb = select_bias ? select_bias[e] : 0.f;
-        key = s + sb;
-        sc = s;
-        // |sigmoid(z+d)-sigmoid(z)| <= s(1-s)|d| + d^2/16 ; fp32 evaluation of
-        // the sigmoid and of the bias add is good to a few ulp of 1+|sb|
-        eps = ez * (s * (1.f - s) + ez + 16.f * kUlp) + 16.f * kUlp * (1.f + fabsf(sb));
-      }
+      const float wn = c.have_norms ? gate_norm(c, wnorm2, e) : 0.f;
+      fast_key_one(c, z, xn, wn, logit_bias, select_bias, e, key, eps, sc);
     }
     K.key[i] = key; K.eps[i] = eps; K.sc[i] = sc;
   }
@@ -1238,8 +1300,8 @@ void launch_select_and_recheck(const SelCfg& sc, const moe_config& c, int T, con
                                const float* logits, int32_t* ids, float* w, const RouteWs& ws,
                                hipStream_t s) {
   MOE_LAUNCH(MOE_K_SELECT, route_select_kernel<EPL>, dim3((T + 3) / 4), dim3(256), 0, s, sc, T, logits,
-                     logit_bias, select_bias, ws.xnorm2, ws.wnorm2, ids, w, ws.counters,
-                     ws.recheck, ws.recheck_low);
+             logit_bias, select_bias, ws.xnorm2, ws.wnorm2, ids, w, ws.counters, ws.recheck,
+             ws.recheck_low);
   // short batches have short lists: a workgroup per listed token, its wavefronts
   // sharing each dot product; otherwise four tokens per workgroup at a time
   const bool coop = T <= 1024 && !logits_in;
@@ -1268,7 +1330,7 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
   SelCfg sc;
   sc.E = E; sc.k = c.top_k; sc.score_fn = c.score_fn; sc.renormalize = c.renormalize;
   sc.G = c.n_groups; sc.Kg = c.topk_groups; sc.gn = c.group_score_n; sc.scale = c.routed_scale;
-  sc.chain_err = 0.f; sc.have_norms = 0; sc.nsplit = 1; sc.T = T;
+  sc.chain_err = 0.f; sc.have_norms = 0; sc.nsplit = 1; sc.wsplit = 1; sc.T = T;
   const int epl = (E + 63) / 64;
   // decode-sized batches: the exact gate costs T*E*H fp64 fused multiply-adds,
   // about 0.24 us per 2^20 of them, in one kernel for the whole stage (a workgroup
@@ -1299,13 +1361,17 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
     else launch_route_exact<8>(sc, c, T, x, gate_w, logit_bias, select_bias, ids, w, ws, s);
     return hipGetLastError();
   }
-  const void* gw_for_norm = logits_in ? nullptr : gate_w;
-  if (bf16)
-    MOE_LAUNCH(MOE_K_GATE_NORMS, gate_wnorm_kernel<true>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm, E,
-                       H, ws.wnorm2, ws.counters);
-  else
-    MOE_LAUNCH(MOE_K_GATE_NORMS, gate_wnorm_kernel<false>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm,
-                       E, H, ws.wnorm2, ws.counters);
+  // The bf16 gate GEMM sums the gate rows' squares and clears the counter itself
+  // (its first token tile); the fp32 gate and the given-logits path use this kernel.
+  if (logits_in || !bf16) {
+    const void* gw_for_norm = logits_in ? nullptr : gate_w;
+    if (bf16)
+      MOE_LAUNCH(MOE_K_GATE_NORMS, gate_wnorm_kernel<true>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm,
+                 E, H, ws.wnorm2, ws.counters);
+    else
+      MOE_LAUNCH(MOE_K_GATE_NORMS, gate_wnorm_kernel<false>, dim3((E + 3) / 4), dim3(256), 0, s, gw_for_norm,
+                 E, H, ws.wnorm2, ws.counters);
+  }
   if (!logits_in) {
     logits = ws.logits;
     sc.have_norms = 1;
@@ -1326,13 +1392,14 @@ hipError_t launch_route(const moe_config& c, int T, const void* x, const void* g
         constexpr int lds = NS * (GBM + GBN) * 8 * 16;
         MOE_LAUNCH(MOE_K_GATE_GEMM, (gate_dma_kernel<GBM, NS, kGateChainSteps>), grid, dim3(512), lds, s,
                    static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
-                   ws.logits, ws.xnorm2);
+                   ws.logits, ws.xnorm2, ws.wnorm2, ws.counters);
       } else {
         MOE_LAUNCH(MOE_K_GATE_GEMM, gate_mfma_kernel<kGateChainSteps>, grid, dim3(512), 0, s,
                    static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(gate_w), T, H, E,
-                   ws.logits, ws.xnorm2);
+                   ws.logits, ws.xnorm2, ws.wnorm2, ws.counters);
       }
       sc.nsplit = nsplit;
+      sc.wsplit = nsplit;
       // chains of kGateChainSteps*64 products; +2 for the flush and the store.  The
       // partial dot products of the splits obey sum_s |x_s||w_s| <= |x||w|, so the
       // chain term is unchanged; summing the slabs in fp32 adds one ulp of that

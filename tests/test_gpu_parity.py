@@ -358,6 +358,30 @@ def test_fp8_weights_on_both_sides_of_the_kernel_switch(rows_per_expert):
     assert err <= TOL["fp8"]
 
 
+@pytest.mark.parametrize("weight_dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("counts", [[300, 200], [40, 0, 700, 90]])
+def test_ffn_k_split_of_leftover_tiles(counts, weight_dtype):
+    """Few tiles and a long K (16 K steps in both GEMMs): the tall-tile kernel cuts
+    every tile along K into parts whose fp32 partial sums the last part adds up.
+    Outputs against the oracle, and twice the same bits."""
+    w, ids, tw = _forced_counts_case(counts, H=1024, I=1024, seed=31)
+    w = w.replace(weight_dtype=weight_dtype, name="k_split")
+    d = inputs(w)
+    L = make_layer(w, d)
+    x = dev(d["x"])
+    out = host(L.forward(x, (dev(ids), dev(tw)))).copy()
+    torch.cuda.synchronize()
+    check_dispatch(L, ids, w, d["x"])
+    ref, _ = oracle.layer_share(d["x"], ids, tw, 0, w.E, d["experts"])
+    err = rel_err(out, ref)
+    print("counts", counts, weight_dtype, "err %.3e" % err, flush=True)
+    assert err <= TOL[weight_dtype]
+    for _ in range(3):
+        again = host(L.forward(x, (dev(ids), dev(tw))))
+        torch.cuda.synchronize()
+        assert np.array_equal(out, again), "the sum of the parts depends on their arrival order"
+
+
 def _random_workload(seed):
     """A small layer with seeded random shape and gate options (every size a legal
     but awkward one: odd expert counts, k up to 8, ragged token counts, EP ranges)."""
