@@ -99,6 +99,8 @@ def measure(moe, name, steps, warmup, args, full):
     # and which kernel dominates the step.  The shared expert normally runs on a
     # second stream beside the routed path; for this pass everything is put on one
     # stream so that each kernel's duration is its own.
+    if args.one_stream:
+        L.overlap_shared = False
     overlap = L.overlap_shared
     L.overlap_shared = False
     moe.moe_profile_enable(64 * max(steps, 1))
@@ -260,6 +262,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the HIP-graph replay, the next_rows measurements and the per_workload table (profiling runs)")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="keep the shared expert on the main stream in every pass (profiling runs: each "
+                         "kernel's duration is then its own)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
