@@ -874,7 +874,7 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
   __shared__ int xlist_all[4][EPL * 64];
   __shared__ double zx_all[4][EPL * 64];
   __shared__ float2 rint_all[4][EPL * 64];     // key intervals of the listed experts
-  __shared__ double part_all[COOP ? 4 : 1][4]; // COOP: partial dot products of the wavefronts
+  __shared__ double part_all[COOP ? 4 : 1][4]; // COOP: partial dot products of the wavefronts (up to 4 experts)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int* const xlist = xlist_all[wave];
   double* const zx = zx_all[wave];
@@ -886,7 +886,11 @@ __global__ __launch_bounds__(256, 2) void route_recheck_kernel(
   // token row once per batch of CB experts, lane-strided 16-byte pieces, four
   // pieces per lane and expert in flight; the lane sums are combined by a fixed
   // butterfly.
-  constexpr int CB = 4;   // 6 and 8 measured slower (register pressure)
+  // CB experts per walk over the token row.  6 and 8 measured slower (register
+  // pressure); a second instance of this code with CB = 2 for the usual short list
+  // (two picks whose order is in doubt) made the kernel slower as a whole
+  // (re-score 46 -> 64 us on the 256-expert gate at 16384 tokens).
+  constexpr int CB = 4;
   auto exact_logits = [&](int t, int n) {
     if (logits_in) {
       for (int q = lane; q < n; q += 64) {
