@@ -566,6 +566,8 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
       for (int sl = 0; sl < NKK; ++sl) {
         const int set = sl & 1;                              // fragments read in this slot
         __builtin_amdgcn_sched_barrier(0);
+        constexpr int NLD = OPK;
+        const bool loads_here = sl < NSLOT;
         if constexpr (SPREAD) {
           if (sl < NSLOT) {
 #pragma unroll
@@ -579,7 +581,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
           // one MFMA, then the loads while no LDS read of this wavefront is
           // outstanding, then MFMA / LDS read pairs
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          if (SPREAD && sl < NSLOT) __builtin_amdgcn_sched_group_barrier(0x020, OPK, 0);
+          if (SPREAD && loads_here) __builtin_amdgcn_sched_group_barrier(0x020, NLD, 0);
           __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
 #pragma unroll
           for (int i = 0; i < NBW + 1; ++i) {
