@@ -65,6 +65,17 @@ int main() {
   CHECK(moe_combine_stage(&c, T, P, I, F, 2, 0, F, nullptr) == MOE_OK);
   CHECK(moe_combine_stage(&c, T, P, I, F, 3, 0, F, nullptr) == MOE_ERR_INVALID_ARG);
   CHECK(moe_combine_stage(&c, T, P, I, F, 2, 2, F, nullptr) == MOE_ERR_INVALID_ARG);
+  // the entry point without a workspace: its size limit and the argument checks come
+  // before anything touches the device (65 536 tokens x top-2 over 8 experts fit, x top-8 over
+  // 128 local experts of a 128-expert layer is exactly the limit, one chunk more is refused)
+  CHECK(moe_dispatch_noalloc_max_bytes() == (size_t(4) << 20));
+  {
+    moe_config big = c; big.n_experts = 128; big.expert_hi = 128; big.top_k = 8;
+    CHECK(moe_dispatch_noalloc(&big, 65536 + 8, P, I, I, I, I, I, P, nullptr) == MOE_ERR_WORKSPACE);
+    CHECK(moe_dispatch_noalloc(&big, -1, P, I, I, I, I, I, P, nullptr) == MOE_ERR_INVALID_ARG);
+    CHECK(moe_dispatch_noalloc(nullptr, 8, P, I, I, I, I, I, P, nullptr) == MOE_ERR_INVALID_ARG);
+    CHECK(moe_dispatch_noalloc(&big, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == MOE_OK);
+  }
   // every structural rule of the layer description
   moe_config b = c; b.hidden = 100; CHECK(moe_workspace_bytes(&b, T) == 0);
   b = c; b.top_k = 9; CHECK(moe_route(&b, T, P, P, nullptr, nullptr, nullptr, I, F, W, need, nullptr) == MOE_ERR_INVALID_ARG);

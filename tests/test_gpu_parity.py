@@ -382,6 +382,17 @@ def test_ffn_k_split_of_leftover_tiles(counts, weight_dtype):
         assert np.array_equal(out, again), "the sum of the parts depends on their arrival order"
 
 
+def test_mfma_rate_probe_runs_and_is_plausible():
+    """The calibration loop of the MFMA roofline: a rate between a tenth of the
+    published bf16 peak and the peak itself, and argument validation."""
+    import paper_2601_08800_amd as moe
+    tf = moe.moe_probe_mfma_rate(512, 500)
+    print("register-only MFMA loop: %.0f TFLOP/s" % tf, flush=True)
+    assert 250.0 < tf <= 2600.0
+    with pytest.raises(moe.MoEError):
+        moe.moe_probe_mfma_rate(0, 500)
+
+
 def _random_workload(seed):
     """A small layer with seeded random shape and gate options (every size a legal
     but awkward one: odd expert counts, k up to 8, ragged token counts, EP ranges)."""
