@@ -67,7 +67,7 @@ constexpr int kPartFloats = 512 * 128;        // fp32 accumulators of one workgr
 static_assert(kSplitTickets == kFfnSplitSlots && kCUs <= kFfnSplitSlots, "workspace holds one slot per part");
 static_assert(size_t(kPartFloats) * 4 == kFfnPartBytes, "partial-sum slot size");
 #ifndef MOE_SPREAD_SLOTS
-#define MOE_SPREAD_SLOTS 4
+#define MOE_SPREAD_SLOTS 2
 #endif
 #ifndef MOE_RING_EXTRA_A
 #define MOE_RING_EXTRA_A 2
@@ -504,7 +504,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   //     fragments of step j-1 in registers, so that step's stages are free)
   //   slot 0: issue loads | read fragments (j, 0) | MFMAs (j-1, 3)
   //   slot 1: issue loads | read fragments (j, 1) | MFMAs (j, 0)
-  //   slot 2: issue loads | read fragments (j, 2) | MFMAs (j, 1)
+  //   slot 2:               read fragments (j, 2) | MFMAs (j, 1)
   //   slot 3:               read fragments (j, 3) | MFMAs (j, 2)
   // The first LDS reads after a barrier are covered by MFMAs that are already
   // fed, and the load instructions of the step's issue group (which stall a
