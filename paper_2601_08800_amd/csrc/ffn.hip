@@ -302,8 +302,14 @@ __device__ __forceinline__ void wait_vmcnt() {
 // MFMAs that consume them.  Workgroup ids are remapped so that each XCD (own L2)
 // walks a contiguous run of tiles, M tiles of one expert first: neighbours
 // share the expert's weight panel and the activation panel.  Wavefronts w and
-// w+4 share a SIMD: while one of them waits (LDS latency, a load instruction
-// being accepted, the barrier) the other keeps the matrix unit busy.  K step 64
+// w+4 (the two row halves) share a SIMD: while one of them waits (LDS latency, a
+// load instruction being accepted, the barrier) the other keeps the matrix unit
+// busy; on full tiles they do so in turns (see the two forms of the K loop).
+// The operand pointers are __restrict__ on purpose: the compiler then knows that
+// the LDS reads do not alias what the loads-to-LDS write (it cannot see their LDS
+// side) and leaves the waiting for loads to the explicit vmcnt waits; without that
+// it waits for every load in flight in front of each LDS read, which serialises
+// the loop.  K step 64
 // (128-byte rows: whole cache lines per row and load instruction); weights and
 // activations have LDS rings of their own (see Ring).
 // NBW = valid 32-row blocks of this wavefront's 128 rows (0..4).
@@ -498,6 +504,94 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     if (op < NBQ) MOE_LOAD_B(op, kcb * WB, stb + (op * 8 + wave) * 64);
     else if (op < NOPS) MOE_LOAD_A(op - NBQ, kca, sta + ((op - NBQ) * 8 + wave) * 64);
   };
+  // Two forms of the K loop.  Full 256-row tiles of bf16 weights alternate the two
+  // wavefronts of a SIMD between memory and MFMA phases (measured 4-6 % faster on
+  // the long-K GEMM-1, 1 % on GEMM-2).  Shorter tiles, where row half 1 has fewer
+  // MFMAs than row half 0 and the phases would not balance (160-row tiles: 5 %
+  // slower), and e4m3 weights, whose widening makes the memory phase the longer one
+  // (7-9 % slower), keep all wavefronts in one phase with loads, LDS reads and MFMAs
+  // interleaved.
+  constexpr bool kAlternate = !F8 && NB == 8;
+  if constexpr (kAlternate) {
+  // The two wavefronts of a SIMD (w and w+4, the two row halves) take turns: a
+  // step has four phases, each closed by a barrier, and a wavefront alternates
+  // between a memory phase (issue half of its loads, read the operand fragments of
+  // two K sub-steps) and an MFMA phase (the 4 x NBW MFMAs on those fragments); row
+  // half 1 runs one phase behind row half 0, so that at any time one wavefront of a
+  // SIMD feeds the matrix unit while the other one's loads and LDS reads are
+  // accepted:
+  //   phase   row half 0                      row half 1
+  //   4j      loads B(j+SB-1), read (j, 0-1)   MFMAs (j-1, 2-3)
+  //   4j+1    MFMAs (j, 0-1)                   loads B(j+SB-1), read (j, 0-1)
+  //   4j+2    loads A(j+SA-1), read (j, 2-3)   MFMAs (j, 0-1)
+  //   4j+3    MFMAs (j, 2-3)                   loads A(j+SA-1), read (j, 2-3)
+  // Step j+1 must have landed when phase 4j+3 ends: every wavefront waits for its
+  // own loads of that step before that barrier.  A stage is refilled only after
+  // the barrier that follows its last read (B(j-1)'s stage in phase 4j or later,
+  // A(j-1)'s in phase 4j+2 or later).
+  uint4 fa[2][NA], fb[2][2];
+  auto read_half = [&](int ks, int h) {
+    if constexpr (NBW > 0) {
+      const uint4* Ab = ringA + (ks % SA) * AS;
+      const uint4* Bb = ringB + (ks % SB) * BS;
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const int piece = (h * 2 + sub) * 2 + (lane >> 5);
+        fb[sub][0] = Bb[slot_b(brow0 + (lane & 31), piece)];
+        fb[sub][1] = Bb[slot_b(brow1 + (lane & 31), piece)];
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) fa[sub][i] = Ab[slot(arow + i * 32 + (lane & 31), piece)];
+      }
+    }
+  };
+  auto mma_half = [&]() {
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const bf16x8 b0 = __builtin_bit_cast(bf16x8, fb[sub][0]);
+      const bf16x8 b1 = __builtin_bit_cast(bf16x8, fb[sub][1]);
+#pragma unroll
+      for (int i = 0; i < NBW; ++i) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, fa[sub][i]);
+        acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b0, acc[i][0], 0, 0, 0);
+        acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b1, acc[i][1], 0, 0, 0);
+      }
+    }
+  };
+  auto phase_end = [&]() {
+    __builtin_amdgcn_sched_barrier(0);               // nothing of the next phase moves in front of the barrier
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto step = [&](int ks, auto steady_c) {
+    constexpr bool ST = decltype(steady_c)::value;      // this step issues both of its load groups
+    const int kb = ks + SB - 1, ka = ks + SA - 1;
+    __builtin_amdgcn_sched_barrier(0);
+    if (ST || kb < ksteps) issue_b(kb);
+    read_half(ks, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    phase_end();
+    mma_half();
+    __builtin_amdgcn_sched_barrier(0);
+    phase_end();
+    if (ST) issue_a(ka);
+    read_half(ks, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (WM == 1) wait_step(ST);
+    phase_end();
+    mma_half();
+    __builtin_amdgcn_sched_barrier(0);
+    if (WM == 0) wait_step(ST);
+    phase_end();
+  };
+  wait_step(SA - 2 < ksteps);                                 // step 0 has landed
+  phase_end();
+  if (WM == 1) phase_end();                                  // one phase behind row half 0
+  const int steady_steps = ksteps - (SA - 1);
+  int ks = 0;
+  for (; ks < steady_steps; ++ks) step(ks, std::true_type{});
+  for (; ks < ksteps; ++ks) step(ks, std::false_type{});
+  if (WM == 0) phase_end();
+  } else {
   // One turn of the K loop, rotated by a sub-step so that the synchronisation for
   // step j sits in front of the LAST sub-step of step j-1:
   //   wait for the loads of step j, barrier  (every wavefront holds its last
@@ -604,6 +698,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   for (; ks < ksteps; ++ks) turn(ks, std::false_type{});
   if constexpr (NBW > 0) mfmas(1);                           // sub-step 3 of the last step
 
+  }
   // A K-split part leaves its fp32 accumulators in the workspace (register order:
   // 8-byte chunk c of thread t at index c*512 + t, so a wavefront's store is 512
   // contiguous bytes); the part that arrives last adds all parts in the
