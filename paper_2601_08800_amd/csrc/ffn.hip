@@ -528,7 +528,11 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   // Step j+1 must have landed when phase 4j+3 ends: every wavefront waits for its
   // own loads of that step before that barrier.  A stage is refilled only after
   // the barrier that follows its last read (B(j-1)'s stage in phase 4j or later,
-  // A(j-1)'s in phase 4j+2 or later).
+  // A(j-1)'s in phase 4j+2 or later).  That is why all fragments of a half step are
+  // read in the memory phase: a read left for the MFMA phase of row half 1 (phase
+  // 4j+4 for sub-step 3 of step j) would meet row half 0's refill of the same
+  // weight stage; such a variant measured 1 % faster and gave outputs that changed
+  // from run to run on the 16 384-token step.
   uint4 fa[2][NA], fb[2][2];
   auto read_half = [&](int ks, int h) {
     if constexpr (NBW > 0) {

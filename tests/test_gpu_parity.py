@@ -382,6 +382,31 @@ def test_ffn_k_split_of_leftover_tiles(counts, weight_dtype):
         assert np.array_equal(out, again), "the sum of the parts depends on their arrival order"
 
 
+def test_ffn_many_full_tiles_same_bits_every_time():
+    """Hundreds of full 256-row tiles with 64 / 16 K steps, more than one round of
+    tiles per CU: the form of the K loop in which the two wavefronts of a SIMD run in
+    different phases.  A stage of the operand rings refilled while the other row half
+    still reads it would show as outputs that change from run to run; outputs
+    against the oracle on sampled tokens, and five times the same bits."""
+    w, ids, tw = _forced_counts_case([1536] * 8, H=4096, I=1024, seed=57)
+    w = w.replace(name="full_tiles")
+    d = inputs(w)
+    L = make_layer(w, d)
+    x = dev(d["x"])
+    out = host(L.forward(x, (dev(ids), dev(tw)))).copy()
+    torch.cuda.synchronize()
+    check_dispatch(L, ids, w, d["x"])
+    tokens = np.random.default_rng(3).choice(w.T, 768, replace=False)
+    ref = oracle_out_for_tokens(w, d, tokens, ids, tw)
+    err = rel_err(out[tokens], ref)
+    print("768 tokens: err %.3e" % err, flush=True)
+    assert err <= TOL["bf16"]
+    for _ in range(5):
+        again = host(L.forward(x, (dev(ids), dev(tw))))
+        torch.cuda.synchronize()
+        assert np.array_equal(out, again), "outputs differ between runs"
+
+
 def test_mfma_rate_probe_runs_and_is_plausible():
     """The calibration loop of the MFMA roofline: a rate between a tenth of the
     published bf16 peak and the peak itself, and argument validation."""
