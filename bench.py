@@ -234,6 +234,8 @@ def measure(moe, name, steps, warmup, args, full):
         out["next_rows"] = next_rows(moe, L, w, x, a_loc, tokens_local, max(steps, 5))
         if forced is not None:
             out["route_separately"] = route_separately(moe, L, x, max(steps, 5))
+        if w.act_dtype == "bf16":
+            out["library_gemm"] = library_gemm(w, a_loc, tokens_local)
     # what the matrix units of this machine sustain with nothing else going on (a
     # register-only MFMA loop, ~10 ms so that the clock settles): the power-limited
     # ceiling of any bf16 GEMM here, beside the published peak the roofline is priced at
@@ -296,6 +298,37 @@ def main():
         out["per_workload"] = table
     print(json.dumps(out), flush=True)
     return 0
+
+
+def library_gemm(w, a_loc, tokens_local):
+    """Context, not part of the path and not a target: the vendor library's dense bf16
+    GEMM (torch.matmul) on ONE matrix with the row count of this workload's GEMM-1 and
+    GEMM-2 (routed rows + shared-expert rows as a single group), 40 launches after 40
+    warm-up launches, Gaussian operands like the workload's."""
+    import torch
+    rows = a_loc + (w.T if w.shared_expert else 0)
+    if rows < 1:
+        return None
+    res = {"rows": rows, "note": "torch.matmul, one dense group of all rows; the path's GEMMs are ragged groups"}
+    gen_ = torch.Generator(device="cuda").manual_seed(7)
+    for name, n, k in (("gemm1", 2 * w.I_loc, w.H), ("gemm2", w.H, w.I_loc)):
+        try:
+            a = (torch.randn(rows, k, device="cuda", generator=gen_) * 0.5).to(torch.bfloat16)
+            b = (torch.randn(n, k, device="cuda", generator=gen_) * 0.02).to(torch.bfloat16)
+            for _ in range(40):
+                c = a @ b.t()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(40):
+                c = a @ b.t()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / 40
+            res[name] = {"us": round(us, 1), "TFLOPs": round(2.0 * rows * n * k / us / 1e6, 1)}
+            del a, b, c
+        except Exception as exc:
+            res[name] = {"error": str(exc)[:200]}
+    return res
 
 
 def route_separately(moe, L, x, steps):

@@ -407,6 +407,28 @@ def test_ffn_many_full_tiles_same_bits_every_time():
         assert np.array_equal(out, again), "outputs differ between runs"
 
 
+@pytest.mark.parametrize("H,I", [(64, 64), (128, 64), (64, 192), (192, 128), (320, 64)])
+def test_ffn_full_tiles_short_k(H, I):
+    """Full 256-row tiles whose K loops have one to five steps: fewer steps than the
+    operand rings have stages, so the alternating form of the loop runs its fill and
+    drain paths only (no steady step at all for one and two steps)."""
+    w, ids, tw = _forced_counts_case([512, 256, 768], H=H, I=I, seed=23)
+    w = w.replace(name="short_k")
+    d = inputs(w)
+    L = make_layer(w, d)
+    x = dev(d["x"])
+    out = host(L.forward(x, (dev(ids), dev(tw)))).copy()
+    torch.cuda.synchronize()
+    check_dispatch(L, ids, w, d["x"])
+    ref, _ = oracle.layer_share(d["x"], ids, tw, 0, w.E, d["experts"])
+    err = rel_err(out, ref)
+    print("H", H, "I", I, "err %.3e" % err, flush=True)
+    assert err <= TOL["bf16"]
+    again = host(L.forward(x, (dev(ids), dev(tw))))
+    torch.cuda.synchronize()
+    assert np.array_equal(out, again)
+
+
 def test_mfma_rate_probe_runs_and_is_plausible():
     """The calibration loop of the MFMA roofline: a rate between a tenth of the
     published bf16 peak and the peak itself, and argument validation."""
