@@ -561,11 +561,18 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
       }
     }
   };
-  auto phase_end = [&]() {
+  // `drain`: this wavefront's LDS reads must have returned before the barrier
+  // (the stage they read is refilled in the next phase).  Otherwise they may
+  // still be in flight when the barrier is passed: the MFMAs that use them wait
+  // for them one by one.
+  auto phase_end = [&](auto drain_c) {
     __builtin_amdgcn_sched_barrier(0);               // nothing of the next phase moves in front of the barrier
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if constexpr (decltype(drain_c)::value) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_barrier" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
   };
+  constexpr std::true_type drain{};
+  constexpr std::false_type no_drain{};
   auto step = [&](int ks, auto steady_c) {
     constexpr bool ST = decltype(steady_c)::value;      // this step issues both of its load groups
     const int kb = ks + SB - 1, ka = ks + SA - 1;
@@ -573,28 +580,30 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     if (ST || kb < ksteps) issue_b(kb);
     read_half(ks, 0);
     __builtin_amdgcn_sched_barrier(0);
-    phase_end();
+    phase_end(no_drain);
     mma_half();
     __builtin_amdgcn_sched_barrier(0);
-    phase_end();
+    phase_end(no_drain);
     if (ST) issue_a(ka);
     read_half(ks, 1);
     __builtin_amdgcn_sched_barrier(0);
     if (WM == 1) wait_step(ST);
-    phase_end();
+    // row half 1 reads the last fragments of this step's weight stage here, and
+    // row half 0 refills that stage in the next phase
+    if constexpr (WM == 1) phase_end(drain); else phase_end(no_drain);
     mma_half();
     __builtin_amdgcn_sched_barrier(0);
     if (WM == 0) wait_step(ST);
-    phase_end();
+    phase_end(no_drain);
   };
   wait_step(SA - 2 < ksteps);                                 // step 0 has landed
-  phase_end();
-  if (WM == 1) phase_end();                                  // one phase behind row half 0
+  phase_end(no_drain);
+  if (WM == 1) phase_end(no_drain);                          // one phase behind row half 0
   const int steady_steps = ksteps - (SA - 1);
   int ks = 0;
   for (; ks < steady_steps; ++ks) step(ks, std::true_type{});
   for (; ks < ksteps; ++ks) step(ks, std::false_type{});
-  if (WM == 0) phase_end();
+  if (WM == 0) phase_end(no_drain);
   } else {
   // One turn of the K loop, rotated by a sub-step so that the synchronisation for
   // step j sits in front of the LAST sub-step of step j-1:
