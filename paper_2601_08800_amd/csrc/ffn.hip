@@ -350,13 +350,14 @@ struct SplitJob {
 
 // F8: the weight tile holds e4m3 codes (64-byte rows: four pieces), widened to
 // bf16 on the way from LDS to the matrix unit.
-template <int NB, bool F8 = false> struct Ring {
+// BR: weight rows of a stage (256, or 512 for the wide tiles of short row groups).
+template <int NB, bool F8 = false, int BR = 256> struct Ring {
   static constexpr int kBK = 64;
   static constexpr int kPPR = kBK / 8;                              // 16-byte pieces per activation row
   static constexpr int kPPRB = F8 ? kBK / 16 : kBK / 8;             // ... per weight row
   static constexpr int kARows = NB * 32;
   static constexpr int kASlots = kARows * kPPR;                     // 16-byte slots of an A stage
-  static constexpr int kBSlots = 256 * kPPRB;                       // ... of a B stage
+  static constexpr int kBSlots = BR * kPPRB;                        // ... of a B stage
   static constexpr int kLds = 160 * 1024;
   static constexpr int kFit = kLds / ((kASlots + kBSlots) * 16);
   static constexpr int kSB = kFit > 4 ? 4 : kFit;                   // weight stages
@@ -369,7 +370,7 @@ template <int NB, bool F8 = false> struct Ring {
 // the 128-row block this wavefront's weight rows lie in ([K/128] values).  The
 // scaled weight code * scale is rounded to bf16 before the MFMA (the exact
 // per-block scale would need a second set of accumulators).
-template <bool DUAL, int NB, int WM, bool F8>
+template <bool DUAL, int NB, int WM, bool F8, int BR = 256>
 __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
                                             const char* __restrict__ Be0,
                                             const char* __restrict__ Be1,
@@ -378,20 +379,22 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
                                             uint16_t* __restrict__ C, int N, int K, int row0,
                                             int row1, int n0, uint4* smem, int wave, int kbeg,
                                             int klen, const SplitJob& job) {
+  static_assert(BR == 256 || (BR == 512 && WM == 0 && NB <= 4), "wide tiles: all wavefronts on one row half");
   constexpr int NBW = NB - WM * 4 < 0 ? 0 : (NB - WM * 4 > 4 ? 4 : NB - WM * 4);
-  constexpr int SA = Ring<NB, F8>::kSA, SB = Ring<NB, F8>::kSB;
-  constexpr int KS = Ring<NB, F8>::kBK;              // K step
-  constexpr int PPR = Ring<NB, F8>::kPPR;            // pieces per activation row in LDS
-  constexpr int PPRB = Ring<NB, F8>::kPPRB;          // pieces per weight row in LDS
+  constexpr int HALF = BR / 2;                       // DUAL: gate rows | up rows of a stage
+  constexpr int SA = Ring<NB, F8, BR>::kSA, SB = Ring<NB, F8, BR>::kSB;
+  constexpr int KS = Ring<NB, F8, BR>::kBK;          // K step
+  constexpr int PPR = Ring<NB, F8, BR>::kPPR;        // pieces per activation row in LDS
+  constexpr int PPRB = Ring<NB, F8, BR>::kPPRB;      // pieces per weight row in LDS
   constexpr int RPI = 64 / PPR;                      // rows filled by one load instruction
   constexpr int RPIB = 64 / PPRB;
   constexpr int WB = F8 ? 1 : 2;                     // bytes per weight element
-  constexpr int AS = Ring<NB, F8>::kASlots;          // slots of an A stage
-  constexpr int BS = Ring<NB, F8>::kBSlots;          // slots of a B stage
+  constexpr int AS = Ring<NB, F8, BR>::kASlots;      // slots of an A stage
+  constexpr int BS = Ring<NB, F8, BR>::kBSlots;      // slots of a B stage
   uint4* const ringA = smem;
   uint4* const ringB = smem + SA * AS;
   const int lane = threadIdx.x & 63;
-  const int wn = wave & 3;
+  const int wn = BR == 512 ? wave : wave & 3;        // column block of this wavefront
   const int ksteps = klen / KS;                      // this workgroup's K window starts at kbeg
 
   // LDS row r keeps its piece p at slot p ^ f(r): f = (r/2)&7 for 128-byte rows,
@@ -410,7 +413,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   constexpr int AGROUPS = NB * 32 / RPI;
   constexpr int NAQ = AGROUPS / 8;                   // full rounds of 8 wavefronts
   constexpr int AREM = AGROUPS % 8;                  // wavefronts 0..AREM-1 load one more
-  constexpr int NBQ = 256 / RPIB / 8;                // weight row groups per wavefront
+  constexpr int NBQ = BR / RPIB / 8;                 // weight row groups per wavefront
   const int lrow = lane / PPR;
   // Operands through buffer descriptors: a wave-uniform base per operand (this
   // tile's first row / first weight row, at the K window's start), a 32-bit byte
@@ -420,7 +423,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
   const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<uint16_t*>(A + size_t(row0) * K + kbeg), 0,
       int((size_t(arows - 1) * K + klen) * 2), 0x00020000);
-  const int brows = (N - n0) < 128 * (DUAL ? 1 : 2) ? (N - n0) : 128 * (DUAL ? 1 : 2);
+  const int brows = (N - n0) < HALF * (DUAL ? 1 : 2) ? (N - n0) : HALF * (DUAL ? 1 : 2);
   const __amdgpu_buffer_rsrc_t rsrcB0 = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<char*>(Be0 + (size_t(n0) * K + kbeg) * WB), 0,
       int((size_t(brows - 1) * K + klen) * WB), 0x00020000);
@@ -439,11 +442,11 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
     const int rg = q * 8 + wave;
     const int piece = (lane % PPRB) ^ ((rg * 4 + (lane >> 4)) & (PPRB - 1));
     const int br = rg * RPIB + lane / PPRB;
-    const int bl = (DUAL && br >= 128) ? br - 128 : br;       // row inside its matrix' tile
+    const int bl = (DUAL && br >= HALF) ? br - HALF : br;     // row inside its matrix' tile
     boff[q] = bl * K * WB + piece * 16;
   }
   // weight row groups q: rows q*8*RPIB .. of the stage; the upper half is the up matrix
-  auto b_is_up = [](int q) { return DUAL && q * 8 * RPIB >= 128; };
+  auto b_is_up = [](int q) { return DUAL && q * 8 * RPIB >= HALF; };
 #define MOE_LOAD_A(q, kcol, dst) \
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrcA, (lptr_t)(dst), 16, aoff[q], (kcol) * 2, 0, 0)
 #define MOE_LOAD_B(q, kcolb, dst)                                                                  \
@@ -489,7 +492,7 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
 
   const int arow = WM * 128;
   const int brow0 = DUAL ? wn * 32 : wn * 64;
-  const int brow1 = DUAL ? 128 + wn * 32 : wn * 64 + 32;
+  const int brow1 = DUAL ? HALF + wn * 32 : wn * 64 + 32;
   constexpr int NKK = KS / 16;                       // MFMA sub-steps per K step
 
 #pragma unroll
@@ -819,13 +822,19 @@ __device__ __forceinline__ void gemm8w_body(const uint16_t* __restrict__ A,
 #undef MOE_LOAD_A
 #undef MOE_LOAD_B
 
-template <bool DUAL, int NB, bool F8>
+template <bool DUAL, int NB, bool F8, bool WIDE>
 __device__ __forceinline__ void gemm8w_tile(const uint16_t* A, const char* Be0, const char* Be1,
                                             const float* Se0, const float* Se1, uint16_t* C, int N,
                                             int K, int row0, int row1, int n0, uint4* smem,
                                             int wave, int kbeg, int klen, const SplitJob& job) {
-  if (wave < 4) gemm8w_body<DUAL, NB, 0, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kbeg, klen, job);
-  else gemm8w_body<DUAL, NB, 1, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kbeg, klen, job);
+  if constexpr (WIDE) {
+    // at most four row blocks: all eight wavefronts work on them, each on its own
+    // 32 (DUAL) or 64 weight rows of a 512-row stage
+    gemm8w_body<DUAL, NB, 0, F8, 512>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kbeg, klen, job);
+  } else {
+    if (wave < 4) gemm8w_body<DUAL, NB, 0, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kbeg, klen, job);
+    else gemm8w_body<DUAL, NB, 1, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kbeg, klen, job);
+  }
 }
 
 // Leftover tiles.  The hardware hands workgroups to CUs in the order of their
@@ -836,13 +845,16 @@ __device__ __forceinline__ void gemm8w_tile(const uint16_t* A, const char* Be0, 
 // is derived from the tile count on the device, so there is no host round trip.
 // The same rule spreads a launch of a few tiles (a shared expert at a decode
 // batch) over the chip.
-template <bool DUAL, bool F8>
+// WIDE: tiles of at most 128 rows (the table is built with that height) x 512
+// weight rows, for launches whose groups are short: twice the weight bytes per K
+// step and barrier, half as many tiles.
+template <bool DUAL, bool F8, bool WIDE = false>
 __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
     const uint16_t* __restrict__ A, const void* __restrict__ B0, const void* __restrict__ B1,
     const float* __restrict__ S0, const float* __restrict__ S1, uint16_t* __restrict__ C, int N,
     int K, const int32_t* __restrict__ tiles, int m_fastest, float* __restrict__ partial,
     int32_t* __restrict__ tickets) {
-  constexpr int BN = DUAL ? 128 : 256;
+  constexpr int BN = (DUAL ? 128 : 256) * (WIDE ? 2 : 1);
   extern __shared__ uint4 smem[];
   const int n_ntiles = (N + BN - 1) / BN;
   const int total = tiles[0] * n_ntiles;
@@ -913,23 +925,32 @@ __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
   const float* Se1 = nullptr;
   if constexpr (F8) {
     const int nkb = K / 128, nnb = N / 128;
-    int nb = (n0 + (wave & 3) * (DUAL ? 32 : 64)) / 128;
+    int nb = (n0 + (WIDE ? wave : wave & 3) * (DUAL ? 32 : 64)) / 128;
     nb = nb < nnb ? nb : nnb - 1;
     Se0 = S0 + (size_t(e) * nnb + nb) * nkb + (kb >> 1);
     Se1 = DUAL ? S1 + (size_t(e) * nnb + nb) * nkb + (kb >> 1) : Se0;
   }
 #define MOE_TILE_(NBV)                                                                        \
-  gemm8w_tile<DUAL, NBV, F8>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave, kb * 64, \
-                             (ke - kb) * 64, job)
-  switch ((row1 - row0 + 31) >> 5) {     // valid 32-row blocks of the tile
-    case 1: MOE_TILE_(1); break;
-    case 2: MOE_TILE_(2); break;
-    case 3: MOE_TILE_(3); break;
-    case 4: MOE_TILE_(4); break;
-    case 5: MOE_TILE_(5); break;
-    case 6: MOE_TILE_(6); break;
-    case 7: MOE_TILE_(7); break;
-    default: MOE_TILE_(8); break;
+  gemm8w_tile<DUAL, NBV, F8, WIDE>(A, Be0, Be1, Se0, Se1, C, N, K, row0, row1, n0, smem, wave,   \
+                                   kb * 64, (ke - kb) * 64, job)
+  if constexpr (WIDE) {
+    switch ((row1 - row0 + 31) >> 5) {   // valid 32-row blocks of the tile: at most four
+      case 1: MOE_TILE_(1); break;
+      case 2: MOE_TILE_(2); break;
+      case 3: MOE_TILE_(3); break;
+      default: MOE_TILE_(4); break;
+    }
+  } else {
+    switch ((row1 - row0 + 31) >> 5) {   // valid 32-row blocks of the tile
+      case 1: MOE_TILE_(1); break;
+      case 2: MOE_TILE_(2); break;
+      case 3: MOE_TILE_(3); break;
+      case 4: MOE_TILE_(4); break;
+      case 5: MOE_TILE_(5); break;
+      case 6: MOE_TILE_(6); break;
+      case 7: MOE_TILE_(7); break;
+      default: MOE_TILE_(8); break;
+    }
   }
 #undef MOE_TILE_
 }
@@ -1230,23 +1251,30 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   // GEMM-2 (K = I_loc is short, N = H wide) is best with 256-row tiles throughout
   // (measured); when the two heights differ a second workgroup of the table
   // kernel builds GEMM-2's table.
-  const int bm = rows_capacity / n_experts <= 320 ? 160 : 256;
-  const int bm2 = 256;
+  // Short groups (at most 128 rows per expert on average: a decode batch
+  // or a cold EP share) take 128-row tiles x 512 weight rows in a GEMM whose
+  // experts still give at least one tile per CU at that width; otherwise the
+  // narrower tiles keep more CUs streaming.
+  const bool few_rows = rows_capacity / n_experts <= 128;
+  const bool wide1 = few_rows && long(n_experts) * ((I + 255) / 256) >= kCUs;
+  const bool wide2 = few_rows && long(n_experts) * ((H + 511) / 512) >= kCUs;
+  const int bm = wide1 ? 128 : (rows_capacity / n_experts <= 320 ? 160 : 256);
+  const int bm2 = wide2 ? 128 : 256;
   const int max_mt = rows_capacity / bm + n_experts;
   const int max_mt2 = rows_capacity / bm2 + n_experts;
   const int cap = max_mt < ws.max_tiles ? max_mt : ws.max_tiles;
   int32_t* const tiles2 = bm2 == bm ? ws.tiles : ws.tiles2;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(bm2 == bm ? 1 : 2), dim3(256), 0, s, offsets,
              n_experts, bm, rows_capacity, ws.tiles, cap, 1, bm2, tiles2, ws.tickets);
-  const int nt1 = (I + 127) / 128, nt2 = (H + 255) / 256;
+  const int nt1 = wide1 ? (I + 255) / 256 : (I + 127) / 128, nt2 = wide2 ? (H + 511) / 512 : (H + 255) / 256;
   constexpr int lds = 160 * 1024;         // all of a CU's LDS: the rings of the tallest tile fill it
   // room for the parts of the leftover tiles behind the whole tiles
   const int g1 = (max_mt * nt1 + 7) / 8 * 8 + kCUs, g2 = (max_mt2 * nt2 + 7) / 8 * 8 + kCUs;
-  auto k1 = ffn_gemm8w_kernel<true, F8>;
-  auto k2 = ffn_gemm8w_kernel<false, F8>;
-  static uint64_t opted1 = 0, opted2 = 0;
-  lds_opt_in(reinterpret_cast<const void*>(k1), lds, opted1);
-  lds_opt_in(reinterpret_cast<const void*>(k2), lds, opted2);
+  auto k1 = wide1 ? ffn_gemm8w_kernel<true, F8, true> : ffn_gemm8w_kernel<true, F8, false>;
+  auto k2 = wide2 ? ffn_gemm8w_kernel<false, F8, true> : ffn_gemm8w_kernel<false, F8, false>;
+  static uint64_t opted1 = 0, opted2 = 0, opted1w = 0, opted2w = 0;
+  lds_opt_in(reinterpret_cast<const void*>(k1), lds, wide1 ? opted1w : opted1);
+  lds_opt_in(reinterpret_cast<const void*>(k2), lds, wide2 ? opted2w : opted2);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
              w_gate, w_up, s_gate, s_up, static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1,
              ws.partial, ws.tickets);

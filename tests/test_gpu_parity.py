@@ -429,6 +429,67 @@ def test_ffn_full_tiles_short_k(H, I):
     assert np.array_equal(out, again)
 
 
+@pytest.mark.parametrize("weight_dtype", ["bf16", "fp8"])
+def test_ffn_wide_tiles_of_short_groups(weight_dtype):
+    """128 local experts with 0 to 200 rows each (76 on average), hidden 1024 and
+    intermediate 512: short groups and enough experts for one 512-weight-row tile per
+    CU, so both GEMMs take their wide tiles (at most 128 rows x 512 weight rows, all
+    eight wavefronts on one row half).  Rows on both sides of the 32-row blocks and of
+    the 128-row tile height; outputs against the oracle on sampled tokens that include
+    every expert's first and last row."""
+    rng = np.random.default_rng(77)
+    counts = [int(rng.choice([0, 1, 13, 31, 32, 33, 64, 96, 127, 128, 129, 200])) for _ in range(128)]
+    w, ids, tw = _forced_counts_case(counts, H=1024, I=512, seed=41)
+    w = w.replace(name="wide_tiles", weight_dtype=weight_dtype)
+    assert 12 < w.T // 128 <= 128
+    d = inputs(w)
+    L = make_layer(w, d)
+    x = dev(d["x"])
+    out = host(L.forward(x, (dev(ids), dev(tw)))).copy()
+    torch.cuda.synchronize()
+    c, offsets, perm, inv = check_dispatch(L, ids, w, d["x"])
+    assert c.tolist() == counts
+    edge = [perm[o] for e in range(128) if counts[e] for o in (offsets[e], offsets[e + 1] - 1)]
+    tokens = np.unique(np.concatenate([np.asarray(edge, dtype=np.int64),
+                                       rng.choice(w.T, 400, replace=False)]))
+    ref = oracle_out_for_tokens(w, d, tokens, ids, tw)
+    err = rel_err(out[tokens], ref)
+    print(weight_dtype, "%d tokens: err %.3e" % (len(tokens), err), flush=True)
+    assert err <= TOL[weight_dtype]
+    again = host(L.forward(x, (dev(ids), dev(tw))))
+    torch.cuda.synchronize()
+    assert np.array_equal(out, again)
+
+
+@pytest.mark.parametrize("weight_dtype", ["bf16", "fp8"])
+def test_ffn_wide_tiles_with_k_split(weight_dtype):
+    """64 experts, hidden 3072, intermediate 1024: GEMM-1 takes wide tiles (70 row
+    tiles x 4 column tiles = 280, 24 more than the CUs) and cuts the 24 leftover tiles
+    along its 48 K steps into two parts each."""
+    counts = [50] * 64
+    for e in (3, 17, 20, 33, 48, 60):
+        counts[e] = 200
+    w, ids, tw = _forced_counts_case(counts, H=3072, I=1024, seed=5)
+    w = w.replace(name="wide_split", weight_dtype=weight_dtype)
+    d = inputs(w)
+    L = make_layer(w, d)
+    x = dev(d["x"])
+    out = host(L.forward(x, (dev(ids), dev(tw)))).copy()
+    torch.cuda.synchronize()
+    c, offsets, perm, inv = check_dispatch(L, ids, w, d["x"])
+    edge = [perm[o] for e in range(64) for o in (offsets[e], offsets[e + 1] - 1)]
+    tokens = np.unique(np.concatenate([np.asarray(edge, dtype=np.int64),
+                                       np.random.default_rng(1).choice(w.T, 300, replace=False)]))
+    ref = oracle_out_for_tokens(w, d, tokens, ids, tw)
+    err = rel_err(out[tokens], ref)
+    print(weight_dtype, "err %.3e" % err, flush=True)
+    assert err <= TOL[weight_dtype]
+    for _ in range(3):
+        again = host(L.forward(x, (dev(ids), dev(tw))))
+        torch.cuda.synchronize()
+        assert np.array_equal(out, again), "the sum of the parts depends on their arrival order"
+
+
 def test_mfma_rate_probe_runs_and_is_plausible():
     """The calibration loop of the MFMA roofline: a rate between a tenth of the
     published bf16 peak and the peak itself, and argument validation."""
