@@ -14,7 +14,8 @@
 // loads a gate tile and the matching up tile so that one lane holds g and u of
 // the same element and the SwiGLU is applied in registers.  Three kernels, by
 // rows per expert: ffn_gemm8w_kernel (prefill: up to 256 rows x 256 weight rows
-// per workgroup, operands global -> LDS directly, LDS rings), ffn_skinny_kernel
+// per workgroup, operands global -> LDS directly, LDS rings; for short groups of
+// many experts up to 128 rows x 512 weight rows), ffn_skinny_kernel
 // (decode and fp8 weights: weight streaming, K split across wavefronts, no LDS
 // staging) and the register-staged ffn_gemm_kernel for the shapes in between.
 // fp8 weights: the weight-streaming kernel widens the e4m3 codes to bf16 in
