@@ -1263,7 +1263,9 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   const int bm2 = wide2 ? 128 : 256;
   const int max_mt = rows_capacity / bm + n_experts;
   const int max_mt2 = rows_capacity / bm2 + n_experts;
-  const int cap = max_mt < ws.max_tiles ? max_mt : ws.max_tiles;
+  // one bound for both tables: the one with the shorter tiles can hold more
+  const int most = max_mt > max_mt2 ? max_mt : max_mt2;
+  const int cap = most < ws.max_tiles ? most : ws.max_tiles;
   int32_t* const tiles2 = bm2 == bm ? ws.tiles : ws.tiles2;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(bm2 == bm ? 1 : 2), dim3(256), 0, s, offsets,
              n_experts, bm, rows_capacity, ws.tiles, cap, 1, bm2, tiles2, ws.tickets);

@@ -490,6 +490,28 @@ def test_ffn_wide_tiles_with_k_split(weight_dtype):
         assert np.array_equal(out, again), "the sum of the parts depends on their arrival order"
 
 
+def test_ffn_second_tile_table_holds_more_tiles_than_the_first():
+    """64 experts alternating 129 rows and one row, hidden 2048, intermediate 512:
+    GEMM-2 takes wide tiles (128-row tiles: 96 of them) while GEMM-1 keeps 160-row
+    tiles (64), so the second table is the longer one; the last experts' rows are
+    the ones a table cut at the first table's bound would lose."""
+    counts = [129, 1] * 32
+    w, ids, tw = _forced_counts_case(counts, H=2048, I=512, seed=9)
+    w = w.replace(name="two_tables")
+    d = inputs(w)
+    L = make_layer(w, d)
+    out = host(L.forward(dev(d["x"]), (dev(ids), dev(tw)))).copy()
+    torch.cuda.synchronize()
+    c, offsets, perm, inv = check_dispatch(L, ids, w, d["x"])
+    edge = [perm[o] for e in range(64) for o in (offsets[e], offsets[e + 1] - 1)]
+    tokens = np.unique(np.concatenate([np.asarray(edge, dtype=np.int64), perm[offsets[56]:offsets[64]],
+                                       np.random.default_rng(2).choice(w.T, 200, replace=False)]))
+    ref = oracle_out_for_tokens(w, d, tokens, ids, tw)
+    err = rel_err(out[tokens], ref)
+    print("%d tokens: err %.3e" % (len(tokens), err), flush=True)
+    assert err <= TOL["bf16"]
+
+
 def test_mfma_rate_probe_runs_and_is_plausible():
     """The calibration loop of the MFMA roofline: a rate between a tenth of the
     published bf16 peak and the peak itself, and argument validation."""
