@@ -14,8 +14,8 @@
 // loads a gate tile and the matching up tile so that one lane holds g and u of
 // the same element and the SwiGLU is applied in registers.  Three kernels, by
 // rows per expert: ffn_gemm8w_kernel (prefill: up to 256 rows x 256 weight rows
-// per workgroup, operands global -> LDS directly, LDS rings; for short groups of
-// many experts up to 128 rows x 512 weight rows), ffn_skinny_kernel
+// per workgroup, operands global -> LDS directly, LDS rings; GEMM-2 of short groups
+// of many experts: up to 128 rows x 512 weight rows), ffn_skinny_kernel
 // (decode and fp8 weights: weight streaming, K split across wavefronts, no LDS
 // staging) and the register-staged ffn_gemm_kernel for the shapes in between.
 // fp8 weights: the weight-streaming kernel widens the e4m3 codes to bf16 in
@@ -847,8 +847,8 @@ __device__ __forceinline__ void gemm8w_tile(const uint16_t* A, const char* Be0, 
 // The same rule spreads a launch of a few tiles (a shared expert at a decode
 // batch) over the chip.
 // WIDE: tiles of at most 128 rows (the table is built with that height) x 512
-// weight rows, for launches whose groups are short: twice the weight bytes per K
-// step and barrier, half as many tiles.
+// weight rows, for GEMM-2 launches whose groups are short: twice the weight bytes
+// per K step and barrier, half as many tiles.
 template <bool DUAL, bool F8, bool WIDE = false>
 __global__ __launch_bounds__(512) void ffn_gemm8w_kernel(
     const uint16_t* __restrict__ A, const void* __restrict__ B0, const void* __restrict__ B1,
@@ -1252,14 +1252,16 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   // GEMM-2 (K = I_loc is short, N = H wide) is best with 256-row tiles throughout
   // (measured); when the two heights differ a second workgroup of the table
   // kernel builds GEMM-2's table.
-  // Short groups (at most 128 rows per expert on average: a decode batch
-  // or a cold EP share) take 128-row tiles x 512 weight rows in a GEMM whose
-  // experts still give at least one tile per CU at that width; otherwise the
-  // narrower tiles keep more CUs streaming.
-  const bool few_rows = rows_capacity / n_experts <= 128;
-  const bool wide1 = few_rows && long(n_experts) * ((I + 255) / 256) >= kCUs;
-  const bool wide2 = few_rows && long(n_experts) * ((H + 511) / 512) >= kCUs;
-  const int bm = wide1 ? 128 : (rows_capacity / n_experts <= 320 ? 160 : 256);
+  // GEMM-2 of short groups (at most 96 rows per expert on average: a decode batch or
+  // a cold EP share) takes 128-row tiles x 512 weight rows when the experts still
+  // give at least one such tile per CU; otherwise the narrower tiles keep more CUs
+  // streaming.  Measured on the 128-expert layer (hidden 2048, I 768, bf16): 85 ->
+  // 81, 94 -> 86, 102 -> 92 us at 32 / 64 / 96 rows per expert, 110 -> 115 us at 128;
+  // e4m3 weights at 64 rows per expert (32 experts, hidden 7168): 73 -> 61 us.
+  // GEMM-1 keeps the narrow tiles: its wide form was slower at every size (the
+  // 512-row bf16 stage leaves room for two ring stages only).
+  const bool wide2 = rows_capacity / n_experts <= 96 && long(n_experts) * ((H + 511) / 512) >= kCUs;
+  const int bm = rows_capacity / n_experts <= 320 ? 160 : 256;
   const int bm2 = wide2 ? 128 : 256;
   const int max_mt = rows_capacity / bm + n_experts;
   const int max_mt2 = rows_capacity / bm2 + n_experts;
@@ -1269,14 +1271,14 @@ void launch_mfma256(const moe_config& c, int n_experts, const void* xs, const in
   int32_t* const tiles2 = bm2 == bm ? ws.tiles : ws.tiles2;
   MOE_LAUNCH(MOE_K_FFN_TILES, ffn_tiles_kernel, dim3(bm2 == bm ? 1 : 2), dim3(256), 0, s, offsets,
              n_experts, bm, rows_capacity, ws.tiles, cap, 1, bm2, tiles2, ws.tickets);
-  const int nt1 = wide1 ? (I + 255) / 256 : (I + 127) / 128, nt2 = wide2 ? (H + 511) / 512 : (H + 255) / 256;
+  const int nt1 = (I + 127) / 128, nt2 = wide2 ? (H + 511) / 512 : (H + 255) / 256;
   constexpr int lds = 160 * 1024;         // all of a CU's LDS: the rings of the tallest tile fill it
   // room for the parts of the leftover tiles behind the whole tiles
   const int g1 = (max_mt * nt1 + 7) / 8 * 8 + kCUs, g2 = (max_mt2 * nt2 + 7) / 8 * 8 + kCUs;
-  auto k1 = wide1 ? ffn_gemm8w_kernel<true, F8, true> : ffn_gemm8w_kernel<true, F8, false>;
+  auto k1 = ffn_gemm8w_kernel<true, F8, false>;
   auto k2 = wide2 ? ffn_gemm8w_kernel<false, F8, true> : ffn_gemm8w_kernel<false, F8, false>;
-  static uint64_t opted1 = 0, opted2 = 0, opted1w = 0, opted2w = 0;
-  lds_opt_in(reinterpret_cast<const void*>(k1), lds, wide1 ? opted1w : opted1);
+  static uint64_t opted1 = 0, opted2 = 0, opted2w = 0;
+  lds_opt_in(reinterpret_cast<const void*>(k1), lds, opted1);
   lds_opt_in(reinterpret_cast<const void*>(k2), lds, wide2 ? opted2w : opted2);
   MOE_LAUNCH(MOE_K_FFN_GEMM1, k1, dim3(g1), dim3(512), lds, s, static_cast<const uint16_t*>(xs),
              w_gate, w_up, s_gate, s_up, static_cast<uint16_t*>(ws.hmid), I, H, ws.tiles, 1,

@@ -433,9 +433,9 @@ def test_ffn_full_tiles_short_k(H, I):
 def test_ffn_wide_tiles_of_short_groups(weight_dtype):
     """128 local experts with 0 to 200 rows each (76 on average), hidden 1024 and
     intermediate 512: short groups and enough experts for one 512-weight-row tile per
-    CU, so both GEMMs take their wide tiles (at most 128 rows x 512 weight rows, all
-    eight wavefronts on one row half).  Rows on both sides of the 32-row blocks and of
-    the 128-row tile height; outputs against the oracle on sampled tokens that include
+    CU, so GEMM-2 takes its wide tiles (at most 128 rows x 512 weight rows, all eight
+    wavefronts on one row half).  Rows on both sides of the 32-row blocks and of the
+    128-row tile height; outputs against the oracle on sampled tokens that include
     every expert's first and last row."""
     rng = np.random.default_rng(77)
     counts = [int(rng.choice([0, 1, 13, 31, 32, 33, 64, 96, 127, 128, 129, 200])) for _ in range(128)]
@@ -462,10 +462,10 @@ def test_ffn_wide_tiles_of_short_groups(weight_dtype):
 
 
 @pytest.mark.parametrize("weight_dtype", ["bf16", "fp8"])
-def test_ffn_wide_tiles_with_k_split(weight_dtype):
-    """64 experts, hidden 3072, intermediate 1024: GEMM-1 takes wide tiles (70 row
-    tiles x 4 column tiles = 280, 24 more than the CUs) and cuts the 24 leftover tiles
-    along its 48 K steps into two parts each."""
+def test_ffn_k_split_beside_wide_tiles(weight_dtype):
+    """64 experts, hidden 3072, intermediate 1024: GEMM-1 (70 row tiles x 8 column
+    tiles = 560, 48 more than two rounds of CUs) cuts the 48 leftover tiles along its
+    48 K steps into two parts each; GEMM-2 takes its wide tiles."""
     counts = [50] * 64
     for e in (3, 17, 20, 33, 48, 60):
         counts[e] = 200
@@ -510,6 +510,34 @@ def test_ffn_second_tile_table_holds_more_tiles_than_the_first():
     err = rel_err(out[tokens], ref)
     print("%d tokens: err %.3e" % (len(tokens), err), flush=True)
     assert err <= TOL["bf16"]
+
+
+def test_ffn_wide_tiles_with_k_split():
+    """32 experts, hidden 4096, intermediate 3072: GEMM-2 takes wide tiles (34 row tiles
+    x 8 column tiles of 512 = 272, 16 more than the CUs) and cuts the 16 leftover tiles
+    along its 48 K steps into two parts each: all eight wavefronts of a part leave
+    partial sums, the last part to arrive adds them."""
+    counts = [60] * 32
+    counts[5] = counts[21] = 200
+    w, ids, tw = _forced_counts_case(counts, H=4096, I=3072, seed=6)
+    w = w.replace(name="wide_split")
+    d = inputs(w)
+    L = make_layer(w, d)
+    x = dev(d["x"])
+    out = host(L.forward(x, (dev(ids), dev(tw)))).copy()
+    torch.cuda.synchronize()
+    c, offsets, perm, inv = check_dispatch(L, ids, w, d["x"])
+    edge = [perm[o] for e in range(32) for o in (offsets[e], offsets[e + 1] - 1)]
+    tokens = np.unique(np.concatenate([np.asarray(edge, dtype=np.int64),
+                                       np.random.default_rng(1).choice(w.T, 100, replace=False)]))
+    ref = oracle_out_for_tokens(w, d, tokens, ids, tw)
+    err = rel_err(out[tokens], ref)
+    print("err %.3e" % err, flush=True)
+    assert err <= TOL["bf16"]
+    for _ in range(3):
+        again = host(L.forward(x, (dev(ids), dev(tw))))
+        torch.cuda.synchronize()
+        assert np.array_equal(out, again), "the sum of the parts depends on their arrival order"
 
 
 def test_mfma_rate_probe_runs_and_is_plausible():
